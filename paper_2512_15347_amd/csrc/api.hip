@@ -1,0 +1,455 @@
+// Host side of the C ABI: configuration checks, per-step coefficient tables, buffer plan and the
+// sequencing of the sampling loop (paper Sec. 5.1 and Sec. 5.2).  No device memory is allocated here.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include "ctx.hpp"
+
+namespace pg {
+
+static thread_local char g_err[512] = "";
+char* error_buffer() { return g_err; }
+pg_status fail(pg_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// ---- per-step scalars of x' = A x + B u + C xi and x_hat = P x + Q u ----
+
+// Rectified flow (Eq. 3) read with tau = noise fraction going 1 -> 0 and v = dx/dtau: the marginal
+// preserving reverse SDE (Eq. 4, RF case of Eq. 12) has drift v + sigma^2/(2 tau) (x + (1-tau) v).
+static void flow_tables(pg_ctx* c) {
+  const int T = c->cfg.T;
+  const double a = c->cfg.noise_level;
+  for (int s = 0; s < T; ++s) {
+    const double tau = 1.0 - (double)s / T, tau_next = 1.0 - (double)(s + 1) / T;
+    const double dt = tau_next - tau;
+    const double sig2 = a * a * tau / std::max(1.0 - tau, 1.0 / T);
+    c->A[s] = 1.0 + sig2 * dt / (2.0 * tau);
+    c->B[s] = dt * (1.0 + sig2 * (1.0 - tau) / (2.0 * tau));
+    c->C[s] = std::sqrt(sig2 * std::fabs(dt));
+    c->Pv[s] = 1.0;          // Eq. 15: x + (remaining time) * v with remaining time = -tau
+    c->Qv[s] = -tau;
+    c->tin[s] = 1000.0 * tau;
+  }
+}
+
+// DDIM(eta) posterior step on a linear beta table (discretisation of Eq. 2 / diffusion case of Eq. 12).
+static void ddim_tables(pg_ctx* c) {
+  const int S = c->cfg.T, Tt = c->cfg.T_train;
+  std::vector<double> abar(Tt);
+  double run = 1.0;
+  for (int i = 0; i < Tt; ++i) {
+    const double beta = (Tt == 1) ? c->cfg.beta0
+                                  : c->cfg.beta0 + (c->cfg.beta1 - c->cfg.beta0) * (double)i / (Tt - 1);
+    run *= 1.0 - beta;
+    abar[i] = run;
+  }
+  auto tstep = [&](int i) { return (int)(((int64_t)(S - i) * (Tt - 1) + S / 2) / S); };
+  const double eta = c->cfg.eta;
+  for (int i = 0; i < S; ++i) {
+    const double at = abar[tstep(i)], ap = abar[tstep(i + 1)];
+    const double s2 = eta * eta * (1.0 - ap) / (1.0 - at) * (1.0 - at / ap);
+    c->A[i] = std::sqrt(ap / at);
+    c->B[i] = std::sqrt(1.0 - ap - s2) - std::sqrt(ap * (1.0 - at) / at);
+    c->C[i] = std::sqrt(s2);
+    c->Pv[i] = 1.0 / std::sqrt(at);               // preview = predicted clean latent
+    c->Qv[i] = -std::sqrt((1.0 - at) / at);
+    c->tin[i] = (double)tstep(i);
+  }
+}
+
+static pg_status build_weight_layout(pg_ctx* c) {
+  const pg_config& f = c->cfg;
+  c->top.assign(PG_W_COUNT, WeightSlot{-1, 0, 0, 0});
+  if (f.net_kind == PG_NET_NONE) { c->weights_numel = 0; return PG_OK; }
+  const int D = f.D, C4 = 4 * f.C;
+  int64_t off = 0;
+  auto put = [&](int id, int rows, int cols) {
+    const int ld = rows > 1 ? ((cols + 63) / 64) * 64 : cols;
+    c->top[id] = WeightSlot{off, rows, cols, ld};
+    off += ((int64_t)rows * ld + 127) / 128 * 128;
+  };
+  put(PG_W_PE_W, D, C4); put(PG_W_PE_B, 1, D); put(PG_W_POS, c->Li, D);
+  put(PG_W_T_W1, D, 256); put(PG_W_T_B1, 1, D); put(PG_W_T_W2, D, D); put(PG_W_T_B2, 1, D);
+  if (f.net_kind == PG_NET_JOINT) { put(PG_W_CTX_W, D, f.Dc); put(PG_W_CTX_B, 1, D); }
+  put(PG_W_FMOD_W, 2 * D, D); put(PG_W_FMOD_B, 1, 2 * D); put(PG_W_F_W, C4, D); put(PG_W_F_B, 1, C4);
+  const int64_t block0 = off;
+  put(PG_W_MOD_W, 6 * D, D); put(PG_W_MOD_B, 1, 6 * D); put(PG_W_QKV_W, 3 * D, D); put(PG_W_QKV_B, 1, 3 * D);
+  put(PG_W_O_W, D, D); put(PG_W_O_B, 1, D); put(PG_W_FC1_W, 4 * D, D); put(PG_W_FC1_B, 1, 4 * D);
+  put(PG_W_FC2_W, D, 4 * D); put(PG_W_FC2_B, 1, D);
+  if (f.net_kind == PG_NET_CROSS) {
+    put(PG_W_CQ_W, D, D); put(PG_W_CQ_B, 1, D); put(PG_W_CKV_W, 2 * D, f.Dc); put(PG_W_CKV_B, 1, 2 * D);
+    put(PG_W_CO_W, D, D); put(PG_W_CO_B, 1, D);
+  }
+  c->block_stride = off - block0;
+  c->weights_numel = block0 + c->block_stride * f.blocks;
+  return PG_OK;
+}
+
+static pg_status validate(const pg_config& f) {
+  if (f.P < 1 || f.N < 1 || f.C < 1 || f.H < 2 || f.W < 2 || f.T < 1)
+    return fail(PG_EINVAL, "P, N, C, T must be >= 1 and H, W >= 2");
+  if (f.N > 64) return fail(PG_ESHAPE, "group size N = %d exceeds 64 (one wavefront per group)", f.N);
+  if ((f.H & 1) || (f.W & 1)) return fail(PG_ESHAPE, "H and W must be even (patch size 2)");
+  if ((int64_t)f.P * f.N > (1 << 24)) return fail(PG_ESHAPE, "too many trajectories");
+  if (!(f.adv_eps > 0.0)) return fail(PG_EINVAL, "adv_eps must be > 0 (Eq. 18)");
+  switch (f.sampler_kind) {
+    case PG_SAMPLER_FLOW:
+      if (!(f.noise_level > 0.0)) return fail(PG_EINVAL, "flow noise level must be > 0: every step needs a log-prob");
+      break;
+    case PG_SAMPLER_DDIM:
+      if (!(f.eta > 0.0)) return fail(PG_EINVAL, "eta must be > 0: every step needs a log-prob");
+      if (!(f.beta0 > 0.0 && f.beta0 <= f.beta1 && f.beta1 < 1.0)) return fail(PG_EINVAL, "need 0 < beta0 <= beta1 < 1");
+      if (f.T_train < f.T + 1) return fail(PG_EINVAL, "T_train = %d must exceed T = %d", f.T_train, f.T);
+      break;
+    case PG_SAMPLER_TABLE:
+      if (!f.tab_A || !f.tab_B || !f.tab_C || !f.tab_P || !f.tab_Q || !f.tab_tin)
+        return fail(PG_EINVAL, "PG_SAMPLER_TABLE needs all six tables");
+      for (int s = 0; s < f.T; ++s)
+        if (!(f.tab_C[s] > 0.0)) return fail(PG_EINVAL, "tab_C[%d] must be > 0", s);
+      break;
+    default: return fail(PG_EINVAL, "unknown sampler_kind %d", f.sampler_kind);
+  }
+  if (f.net_kind != PG_NET_NONE) {
+    if (f.net_kind < PG_NET_ADALN || f.net_kind > PG_NET_JOINT) return fail(PG_EINVAL, "unknown net_kind %d", f.net_kind);
+    if (f.D < 64 || f.D % 64) return fail(PG_ESHAPE, "width D = %d must be a positive multiple of 64", f.D);
+    if (f.blocks < 1 || f.heads < 1 || f.D % f.heads) return fail(PG_ESHAPE, "heads must divide D, blocks >= 1");
+    const int hd = f.D / f.heads;
+    if (hd != 32 && hd != 64) return fail(PG_ESHAPE, "head width %d not supported (32 or 64)", hd);
+    if (f.net_kind == PG_NET_ADALN) {
+      if (f.Lc != 0) return fail(PG_EINVAL, "PG_NET_ADALN takes no context tokens");
+    } else {
+      if (f.Lc < 1) return fail(PG_EINVAL, "context variants need Lc >= 1");
+      if (f.Dc < 64 || f.Dc % 64) return fail(PG_ESHAPE, "context width Dc = %d must be a positive multiple of 64", f.Dc);
+    }
+  }
+  if (f.n_sched < 0 || (f.n_sched > 0 && (!f.sched_group || !f.sched_step || !f.sched_k)))
+    return fail(PG_EINVAL, "schedule arrays missing");
+  return PG_OK;
+}
+
+static pg_status plan_workspace(pg_ctx* c) {
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t o = off; off = align256(off + bytes); return o; };
+  c->ws_partials = take(sizeof(float) * (size_t)c->M0 * chunks_per_traj(c->d));
+  c->ws_k = take(sizeof(int32_t) * c->cfg.P);
+  c->ws_newoff = take(sizeof(int32_t) * (c->cfg.P + 1));
+  c->ws_forced = take(sizeof(uint64_t) * c->cfg.P + sizeof(int32_t) * c->M0);   // masks + sel of the OVF shadow run
+  c->ws_net = off;
+  PG_TRY(net_plan(c));
+  c->ws_total = align256(off + c->net.total);
+  return PG_OK;
+}
+
+}  // namespace pg
+
+using namespace pg;
+
+extern "C" const char* pg_last_error(void) { return error_buffer(); }
+
+extern "C" pg_status pg_create(const pg_config* cfg, pg_ctx** out) {
+  if (out) *out = nullptr;
+  if (!cfg || !out) return fail(PG_EINVAL, "pg_create: null argument");
+  PG_TRY(validate(*cfg));
+  pg_ctx* c = new (std::nothrow) pg_ctx();
+  if (!c) return fail(PG_EINVAL, "out of host memory");
+  c->cfg = *cfg;
+  const pg_config& f = c->cfg;
+  c->d = f.C * f.H * f.W;
+  c->Li = (f.H / 2) * (f.W / 2);
+  c->L = c->Li + (f.net_kind == PG_NET_JOINT ? f.Lc : 0);
+  c->M0 = f.P * f.N;
+  const int T = f.T;
+  c->A.resize(T); c->B.resize(T); c->C.resize(T); c->Pv.resize(T); c->Qv.resize(T); c->tin.resize(T);
+  if (f.sampler_kind == PG_SAMPLER_FLOW) flow_tables(c);
+  else if (f.sampler_kind == PG_SAMPLER_DDIM) ddim_tables(c);
+  else
+    for (int s = 0; s < T; ++s) {
+      c->A[s] = f.tab_A[s]; c->B[s] = f.tab_B[s]; c->C[s] = f.tab_C[s];
+      c->Pv[s] = f.tab_P[s]; c->Qv[s] = f.tab_Q[s]; c->tin[s] = f.tab_tin[s];
+    }
+  for (int s = 0; s < T; ++s)
+    if (!(c->C[s] > 0.0) || !std::isfinite(c->A[s]) || !std::isfinite(c->B[s])) {
+      delete c;
+      return fail(PG_EINVAL, "step %d has a non-positive noise scale or non-finite coefficients", s);
+    }
+  // schedule: per group, steps strictly increasing, counts strictly decreasing below N (Sec. 5.2)
+  c->sched.assign(f.P, {});
+  c->is_checkpoint.assign(T, 0);
+  for (int i = 0; i < f.n_sched; ++i) {
+    const int g = f.sched_group[i], s = f.sched_step[i], k = f.sched_k[i];
+    if (g < 0 || g >= f.P || s < 0 || s >= T || k < 1) {
+      delete c;
+      return fail(PG_ESCHED, "schedule entry %d (group %d, step %d, k %d) out of range", i, g, s, k);
+    }
+    c->sched[g].push_back({s, k});
+    c->is_checkpoint[s] = 1;
+  }
+  for (int g = 0; g < f.P; ++g) {
+    std::sort(c->sched[g].begin(), c->sched[g].end());
+    int prev_k = f.N, prev_s = -1;
+    for (auto& e : c->sched[g]) {
+      if (e.first == prev_s || e.second >= prev_k) {
+        delete c;
+        return fail(PG_ESCHED, "group %d: survivor counts must strictly decrease at distinct steps", g);
+      }
+      prev_s = e.first; prev_k = e.second;
+    }
+  }
+  // nullify host pointers we must not keep
+  c->cfg.tab_A = c->cfg.tab_B = c->cfg.tab_C = c->cfg.tab_P = c->cfg.tab_Q = c->cfg.tab_tin = nullptr;
+  c->cfg.sched_group = c->cfg.sched_step = c->cfg.sched_k = nullptr;
+  pg_status st = build_weight_layout(c);
+  if (st == PG_OK) st = plan_workspace(c);
+  if (st != PG_OK) { delete c; return st; }
+  c->offsets.assign(f.P + 1, 0);
+  *out = c;
+  return PG_OK;
+}
+
+extern "C" void pg_destroy(pg_ctx* c) {
+  if (!c) return;
+  if (c->staging) (void)hipHostFree(c->staging);
+  delete c;
+}
+
+extern "C" size_t pg_workspace_bytes(const pg_ctx* c) { return c ? c->ws_total : 0; }
+extern "C" int64_t pg_weights_numel(const pg_ctx* c) { return c ? c->weights_numel : 0; }
+
+extern "C" pg_status pg_weight_slot(const pg_ctx* c, int32_t id, int32_t block, int64_t* offset,
+                                    int32_t* rows, int32_t* cols, int32_t* ld) {
+  if (!c || id < 0 || id >= PG_W_COUNT) return fail(PG_EINVAL, "pg_weight_slot: bad id");
+  const WeightSlot& w = c->top[id];
+  if (w.offset < 0) return fail(PG_EINVAL, "tensor %d does not exist for this network", id);
+  int64_t off = w.offset;
+  if (id >= PG_W_MOD_W) {
+    if (block < 0 || block >= c->cfg.blocks) return fail(PG_EINVAL, "block %d out of range", block);
+    off += c->block_stride * block;
+  }
+  if (offset) *offset = off;
+  if (rows) *rows = w.rows;
+  if (cols) *cols = w.cols;
+  if (ld) *ld = w.ld;
+  return PG_OK;
+}
+
+extern "C" pg_status pg_get_tables(const pg_ctx* c, double* A, double* B, double* C, double* P, double* Q,
+                                   double* t_in) {
+  if (!c) return fail(PG_EINVAL, "pg_get_tables: null context");
+  const size_t n = sizeof(double) * c->cfg.T;
+  if (A) memcpy(A, c->A.data(), n);
+  if (B) memcpy(B, c->B.data(), n);
+  if (C) memcpy(C, c->C.data(), n);
+  if (P) memcpy(P, c->Pv.data(), n);
+  if (Q) memcpy(Q, c->Qv.data(), n);
+  if (t_in) memcpy(t_in, c->tin.data(), n);
+  return PG_OK;
+}
+
+extern "C" pg_status pg_bind(pg_ctx* c, const pg_buffers* b) {
+  if (!c || !b) return fail(PG_EINVAL, "pg_bind: null argument");
+  c->bound = false;
+  if (!b->x[0] || !b->x[1] || !b->u || !b->orig_id[0] || !b->orig_id[1] || !b->group_offsets ||
+      !b->group_of || !b->rewards || !b->masks || !b->sel_idx || !b->logp_hist || !b->logp_sum || !b->adv ||
+      !b->probe_w || !b->status)
+    return fail(PG_EINVAL, "pg_bind: a required buffer is NULL");
+  if (b->x[0] == b->x[1] || b->orig_id[0] == b->orig_id[1]) return fail(PG_EINVAL, "pg_bind: ping-pong buffers alias");
+  if (c->cfg.net_kind != PG_NET_NONE && (!b->weights || !b->y)) return fail(PG_EINVAL, "pg_bind: weights / y missing");
+  if (c->cfg.net_kind >= PG_NET_CROSS && !b->ctx) return fail(PG_EINVAL, "pg_bind: ctx missing");
+  if (!b->workspace || b->workspace_bytes < c->ws_total)
+    return fail(PG_EWORKSPACE, "workspace of %zu bytes given, %zu needed", b->workspace_bytes, c->ws_total);
+  if (((uintptr_t)b->workspace & 255) || ((uintptr_t)b->x[0] & 15) || ((uintptr_t)b->x[1] & 15) ||
+      ((uintptr_t)b->u & 15) || ((uintptr_t)b->probe_w & 15) || ((uintptr_t)b->weights & 15) ||
+      ((uintptr_t)b->ctx & 15))
+    return fail(PG_ESHAPE, "pg_bind: buffers must be 16-byte aligned (workspace 256)");
+  if (!c->staging) {
+    const size_t n = (size_t)(c->cfg.T + 1) * (2 * c->cfg.P + 2);
+    PG_HIP(hipHostMalloc((void**)&c->staging, n * sizeof(int32_t), hipHostMallocDefault));
+  }
+  c->buf = *b;
+  c->bound = true;
+  c->initialised = false;
+  c->context_ready = false;
+  return PG_OK;
+}
+
+extern "C" pg_status pg_state(const pg_ctx* c, int32_t* M, int32_t* cur_x, int32_t* cur_id,
+                              int32_t* offsets, int64_t* evals, int64_t* updates) {
+  if (!c) return fail(PG_EINVAL, "pg_state: null context");
+  if (M) *M = c->M;
+  if (cur_x) *cur_x = c->cur_x;
+  if (cur_id) *cur_id = c->cur_id;
+  if (offsets) memcpy(offsets, c->offsets.data(), sizeof(int32_t) * (c->cfg.P + 1));
+  if (evals) *evals = c->evals;
+  if (updates) *updates = c->updates;
+  return PG_OK;
+}
+
+static char* ws(pg_ctx* c, size_t off) { return (char*)c->buf.workspace + off; }
+
+extern "C" pg_status pg_init_group(pg_ctx* c, uint64_t seed, void* stream) {
+  if (!c || !c->bound) return fail(PG_EINVAL, "pg_init_group: context not bound");
+  hipStream_t s = (hipStream_t)stream;
+  const pg_config& f = c->cfg;
+  c->seed = seed;
+  c->M = c->M0; c->cur_x = 0; c->cur_id = 0;
+  c->pending_gather = false; c->net_fresh = false;
+  c->evals = 0; c->updates = 0;
+  int32_t* slot = c->staging + (size_t)f.T * (2 * f.P + 2);
+  for (int g = 0; g <= f.P; ++g) { c->offsets[g] = g * f.N; slot[g] = g * f.N; }
+  PG_HIP(hipMemcpyAsync(c->buf.group_offsets, slot, sizeof(int32_t) * (f.P + 1), hipMemcpyHostToDevice, s));
+  PG_TRY(launch_iota(c->buf.orig_id[0], c->M0, s));
+  PG_TRY(launch_fill_group_of(c->buf.group_offsets, f.P, c->buf.group_of, s));
+  PG_TRY(launch_fill_u32(c->buf.logp_hist, 0x7FC00000u, (size_t)f.T * c->M0, s));
+  PG_TRY(launch_fill_u32(c->buf.logp_sum, 0u, (size_t)c->M0, s));
+  PG_TRY(launch_fill_u32(c->buf.status, 0u, 4, s));
+  PG_TRY(pg_init_latents(c->buf.x[0], c->buf.orig_id[0], c->M0, c->d, seed, stream));
+  if (f.net_kind != PG_NET_NONE && !c->context_ready) {
+    PG_TRY(net_prepare(c, s));
+    c->context_ready = true;
+  }
+  c->initialised = true;
+  return PG_OK;
+}
+
+extern "C" pg_status pg_net_forward(pg_ctx* c, int32_t step, void* stream) {
+  if (!c || !c->bound || !c->initialised) return fail(PG_ESCHED, "pg_net_forward: call pg_init_group first");
+  if (step < 0 || step >= c->cfg.T) return fail(PG_EINVAL, "step %d out of range", step);
+  if (c->pending_gather) return fail(PG_ESCHED, "pg_net_forward: a prune is waiting for its pg_step");
+  if (c->cfg.net_kind != PG_NET_NONE) PG_TRY(net_forward(c, step, (hipStream_t)stream));
+  c->net_fresh = true;
+  c->evals += c->M;
+  return PG_OK;
+}
+
+// shared tail of pg_prune / pg_prune_forced once sel_idx and the new offsets are on the device
+static pg_status finish_prune(pg_ctx* c, const std::vector<int>& new_off, hipStream_t s) {
+  const int P = c->cfg.P;
+  const int M_new = new_off[P];
+  PG_TRY(launch_gather_ids(c->buf.orig_id[c->cur_id], c->buf.sel_idx, M_new, c->buf.orig_id[1 - c->cur_id], s));
+  c->cur_id = 1 - c->cur_id;
+  PG_HIP(hipMemcpyAsync(c->buf.group_offsets, ws(c, c->ws_newoff), sizeof(int32_t) * (P + 1),
+                        hipMemcpyDeviceToDevice, s));
+  PG_TRY(launch_fill_group_of(c->buf.group_offsets, P, c->buf.group_of, s));
+  c->offsets = new_off;
+  c->M = M_new;
+  c->pending_gather = true;
+  return PG_OK;
+}
+
+static pg_status prune_common(pg_ctx* c, int step, const uint64_t* forced, uint64_t* ovf_masks_out,
+                              hipStream_t s) {
+  if (!c || !c->bound || !c->initialised) return fail(PG_ESCHED, "pg_prune: call pg_init_group first");
+  const pg_config& f = c->cfg;
+  if (step < 0 || step >= f.T) return fail(PG_EINVAL, "step %d out of range", step);
+  if (!c->net_fresh) return fail(PG_ESCHED, "pg_prune: no network evaluation for the current latents");
+  if (c->pending_gather) return fail(PG_ESCHED, "pg_prune: previous prune not yet consumed by pg_step");
+  const int P = f.P;
+  std::vector<int> k(P), new_off(P + 1, 0);
+  bool any = false;
+  for (int g = 0; g < P; ++g) {
+    const int n = c->offsets[g + 1] - c->offsets[g];
+    k[g] = n;
+    for (auto& e : c->sched[g]) if (e.first == step) { k[g] = e.second; any = true; }
+    if (k[g] > n) {
+      if (!forced) return fail(PG_ESCHED, "group %d holds %d trajectories, schedule asks for %d", g, n, k[g]);
+      k[g] = n;
+    }
+  }
+  if (!any && !forced) return fail(PG_ESCHED, "step %d is not a checkpoint of any group", step);
+  for (int g = 0; g < P; ++g) new_off[g + 1] = new_off[g] + k[g];
+  int32_t* slot = c->staging + (size_t)step * (2 * P + 2);
+  memcpy(slot, k.data(), sizeof(int32_t) * P);
+  memcpy(slot + P, new_off.data(), sizeof(int32_t) * (P + 1));
+  PG_HIP(hipMemcpyAsync(ws(c, c->ws_k), slot, sizeof(int32_t) * P, hipMemcpyHostToDevice, s));
+  PG_HIP(hipMemcpyAsync(ws(c, c->ws_newoff), slot + P, sizeof(int32_t) * (P + 1), hipMemcpyHostToDevice, s));
+  PG_TRY(pg_preview_reward(c->buf.x[c->cur_x], c->buf.u, c->buf.probe_w, c->buf.rewards, c->M, c->d,
+                           c->Pv[step], c->Qv[step], f.probe_bias, (float*)ws(c, c->ws_partials), s));
+  if (!forced) {
+    PG_TRY(launch_ovf(c->buf.rewards, c->buf.group_offsets, (int32_t*)ws(c, c->ws_k), P,
+                      (int32_t*)ws(c, c->ws_newoff), c->buf.masks, c->buf.sel_idx, c->buf.status, s));
+    return finish_prune(c, new_off, s);
+  }
+  // forced survivors: run the OVF into shadow buffers (for the record), then impose the masks
+  uint64_t* shadow_masks = (uint64_t*)ws(c, c->ws_forced);
+  int32_t* shadow_sel = (int32_t*)(ws(c, c->ws_forced) + sizeof(uint64_t) * P);
+  PG_TRY(launch_ovf(c->buf.rewards, c->buf.group_offsets, (int32_t*)ws(c, c->ws_k), P,
+                    (int32_t*)ws(c, c->ws_newoff), shadow_masks, shadow_sel, c->buf.status, s));
+  if (ovf_masks_out)
+    PG_HIP(hipMemcpyAsync(ovf_masks_out, shadow_masks, sizeof(uint64_t) * P, hipMemcpyDeviceToDevice, s));
+  for (int g = 0; g < P; ++g) {
+    const int n = c->offsets[g + 1] - c->offsets[g];
+    const uint64_t valid = (n == 64) ? ~0ull : ((1ull << n) - 1ull);
+    if (forced[g] & ~valid) return fail(PG_EINVAL, "forced mask of group %d names slots beyond its %d members", g, n);
+    const int cnt = __builtin_popcountll(forced[g]);
+    if (cnt < 1) return fail(PG_EINVAL, "forced mask of group %d is empty", g);
+    new_off[g + 1] = new_off[g] + cnt;
+  }
+  PG_HIP(hipStreamSynchronize(s));     // test hook: plain synchronous uploads from caller memory
+  PG_HIP(hipMemcpy(c->buf.masks, forced, sizeof(uint64_t) * P, hipMemcpyHostToDevice));
+  PG_HIP(hipMemcpy(ws(c, c->ws_newoff), new_off.data(), sizeof(int32_t) * (P + 1), hipMemcpyHostToDevice));
+  PG_TRY(launch_masks_to_sel(c->buf.masks, c->buf.group_offsets, (int32_t*)ws(c, c->ws_newoff), P,
+                             c->buf.sel_idx, s));
+  return finish_prune(c, new_off, s);
+}
+
+extern "C" pg_status pg_prune(pg_ctx* c, int32_t step, void* stream) {
+  return prune_common(c, step, nullptr, nullptr, (hipStream_t)stream);
+}
+
+extern "C" pg_status pg_prune_forced(pg_ctx* c, int32_t step, const uint64_t* masks, uint64_t* ovf_masks_out,
+                                     void* stream) {
+  if (!masks) return fail(PG_EINVAL, "pg_prune_forced: masks is NULL");
+  return prune_common(c, step, masks, ovf_masks_out, (hipStream_t)stream);
+}
+
+extern "C" pg_status pg_step(pg_ctx* c, int32_t step, void* stream) {
+  if (!c || !c->bound || !c->initialised) return fail(PG_ESCHED, "pg_step: call pg_init_group first");
+  if (step < 0 || step >= c->cfg.T) return fail(PG_EINVAL, "step %d out of range", step);
+  if (!c->net_fresh) return fail(PG_ESCHED, "pg_step: no network evaluation for the current latents");
+  PG_TRY(pg_sde_step_logprob(c->buf.x[c->cur_x], c->buf.u, c->buf.x[1 - c->cur_x], nullptr,
+                             c->buf.logp_hist + (size_t)step * c->M0, c->buf.logp_sum,
+                             c->pending_gather ? c->buf.sel_idx : nullptr, c->buf.orig_id[c->cur_id], c->M,
+                             c->d, c->A[step], c->B[step], c->C[step], c->seed, (uint32_t)step,
+                             (float*)ws(c, c->ws_partials), stream));
+  c->cur_x = 1 - c->cur_x;
+  c->pending_gather = false;
+  c->net_fresh = false;
+  c->updates += c->M;
+  return PG_OK;
+}
+
+extern "C" pg_status pg_advantages(pg_ctx* c, void* stream) {
+  if (!c || !c->bound || !c->initialised) return fail(PG_ESCHED, "pg_advantages: call pg_init_group first");
+  if (c->pending_gather) return fail(PG_ESCHED, "pg_advantages: a prune is waiting for its pg_step");
+  PG_TRY(pg_preview_reward(c->buf.x[c->cur_x], nullptr, c->buf.probe_w, c->buf.rewards, c->M, c->d, 1.0, 0.0,
+                           c->cfg.probe_bias, (float*)ws(c, c->ws_partials), stream));
+  return pg_group_advantages(c->buf.rewards, c->buf.group_offsets, c->cfg.P, c->cfg.adv_eps, c->buf.adv, stream);
+}
+
+extern "C" pg_status pg_sample_group(pg_ctx* c, uint64_t seed, void* stream) {
+  PG_TRY(pg_init_group(c, seed, stream));
+  for (int s = 0; s < c->cfg.T; ++s) {
+    PG_TRY(pg_net_forward(c, s, stream));
+    if (c->is_checkpoint[s]) PG_TRY(pg_prune(c, s, stream));
+    PG_TRY(pg_step(c, s, stream));
+  }
+  return pg_advantages(c, stream);
+}
+
+extern "C" pg_status pg_check(pg_ctx* c, void* stream) {
+  if (!c || !c->bound) return fail(PG_EINVAL, "pg_check: context not bound");
+  PG_HIP(hipStreamSynchronize((hipStream_t)stream));
+  int32_t st[4] = {0, 0, 0, 0};
+  PG_HIP(hipMemcpy(st, c->buf.status, sizeof(st), hipMemcpyDeviceToHost));
+  if (st[0] & 1) return fail(PG_ENAN, "a non-finite proxy reward reached the selection");
+  if (st[0] & 2) return fail(PG_EINVAL, "the selection met a group with a bad size or count");
+  return PG_OK;
+}
