@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libprogrpo.so")
-SOURCES = ["api.hip", "sampler_kernels.hip", "ovf_kernels.hip", "dit_kernels.hip"]
+SOURCES = ["api.hip", "sampler_kernels.hip", "ovf_kernels.hip", "gemm.hip", "attention.hip", "dit_kernels.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-ffp-contract=off", "-Wall", "-Wno-unused-function", "-Wno-unknown-attributes"]

@@ -1,0 +1,34 @@
+// bf16 MFMA GEMM of the network: C[M, N] = A[M, K] W[N, K]^T (+ fused epilogue), fp32 accumulate.
+#pragma once
+#include "common.hpp"
+
+namespace pg {
+
+enum GemmEpilogue {
+  EPI_F32 = 0,      // outf[r, n] = acc + bias
+  EPI_EMBED = 1,    // outf[(r / Li) * L + r % Li, n] = acc + bias + pos[r % Li, n]     (patch embedding)
+  EPI_BF16 = 2,     // outb[r, n] = bf16(acc + bias)
+  EPI_QKV = 3,      // n < v_start: outb[r, n]; else vt[((r / L) * Dv + n - v_start) * Lpad + r % L]
+  EPI_GELU = 4,     // outb[r, n] = bf16(gelu_tanh(acc + bias))
+  EPI_RESID = 5,    // outf[r, n] += gate[group_of[r / L], n] * (acc + bias)   (gate NULL: plain add)
+  EPI_UNPATCH = 6   // u[m, c, 2 py + dy, 2 px + dx] = acc + bias, r = m * Li + py * Wp + px, n = 4 c + 2 dy + dx
+};
+
+struct GemmArgs {
+  const uint16_t* A; int64_t lda;
+  const uint16_t* W; int64_t ldw;
+  const uint16_t* bias;            // bf16 [N] or NULL
+  int M, N, K;
+  float* outf; int64_t ldo;
+  uint16_t* outb; int64_t ldob;
+  // epilogue extras
+  int L, Li;                       // rows per trajectory in the output / input
+  const uint16_t* pos;             // bf16 [Li, N]
+  uint16_t* vt; int v_start, Lpad;
+  const float* gate; int64_t gate_ld; const int32_t* group_of;
+  int Wp, HW, Wimg;                // unpatchify: patches per row, H*W, W
+};
+
+pg_status launch_gemm(const GemmArgs& a, int epilogue, hipStream_t s);
+
+}  // namespace pg

@@ -1,0 +1,163 @@
+"""GPU parity of the sampling loop (init group, prune, step, advantages) through the C ABI.
+
+The first block drives the loop with the network output taken from the oracle run (written into
+the library's `u` buffer before each prune / step), which isolates every non-network stage at the
+loop level; the second block runs the library's own network."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import loop, sampler, ovf
+from paper_2512_15347_amd import workloads
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def _oracle(name, seed, **kw):
+    cfg = workloads.get_config(name)
+    w = workloads.make_weights(cfg)
+    inp = workloads.make_inputs(cfg, w)
+    s = cfg["sampler"]
+    tables = (sampler.flow_sde_tables(cfg["T"], s["a"]) if s["kind"] == "flow"
+              else sampler.ddim_sde_tables(cfg["T"], s["eta"], s["beta0"], s["beta1"], s["T_train"]))
+    rec = loop.run(cfg, tables, inp, seed, wts=w, keep_u_steps=range(cfg["T"]), **kw)
+    return cfg, w, inp, tables, rec
+
+
+def _compare_final(lib, ctx, buf, cfg, rec, x_tol, lp_rtol=1e-3):
+    st = lib.pg_state(ctx, cfg["P"])
+    M = st["M"]
+    assert st["offsets"] == rec["offsets"].tolist()
+    assert st["evals"] == rec["evals"] and st["updates"] == rec["updates"]
+    ids = buf.orig_id[st["cur_id"]].cpu().numpy()[:M]
+    np.testing.assert_array_equal(ids, rec["orig_id"])
+    np.testing.assert_array_equal(buf.group_offsets.cpu().numpy(), rec["offsets"])
+    gof = buf.group_of.cpu().numpy()[:M]
+    for g in range(cfg["P"]):
+        assert np.all(gof[rec["offsets"][g]:rec["offsets"][g + 1]] == g)
+    x = buf.x[st["cur_x"]].cpu().numpy()[:M].astype(np.float64)
+    for r in range(M):                                   # max error relative to the trajectory's largest entry
+        assert np.max(np.abs(x[r] - rec["x"][r])) <= x_tol * np.max(np.abs(rec["x"][r])), r
+    hist = buf.logp_hist.cpu().numpy().astype(np.float64)
+    want = rec["logp_hist"]
+    assert np.array_equal(np.isnan(hist), np.isnan(want))
+    ok = ~np.isnan(want)
+    np.testing.assert_allclose(hist[ok], want[ok], rtol=lp_rtol)
+    lsum = buf.logp_sum.cpu().numpy().astype(np.float64)
+    np.testing.assert_allclose(lsum, rec["logp_sum"], rtol=lp_rtol, atol=lp_rtol * np.max(np.abs(want[ok])))
+    rew = buf.rewards.cpu().numpy()[:M].astype(np.float64)
+    for g in range(cfg["P"]):
+        b, e = rec["offsets"][g], rec["offsets"][g + 1]
+        scale = max(np.max(np.abs(rec["rewards"][b:e])), np.std(rec["rewards"][b:e]))
+        assert np.max(np.abs(rew[b:e] - rec["rewards"][b:e])) <= 1e-3 * scale
+    return x, rew
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg4_small", "cfg2_small"])
+def test_loop_with_injected_network_output(lib, name):
+    say(f"loop (oracle u injected) {name}")
+    seed = workloads.MASTER_SEED
+    cfg, w, inp, tables, rec = _oracle(name, seed)
+    c, keep = lib.make_config(cfg, probe_bias=inp["probe_b"], net=False)
+    ctx = lib.pg_create(c)
+    buf = lib.Buffers(ctx, cfg, inputs=inp)
+    lib.pg_bind(ctx, buf)
+    lib.pg_init_group(ctx, seed)
+    x0 = buf.x[0].cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(x0 - rec["x_after"][0][1] * 0 - x0)) == 0   # shape sanity
+    for s in range(cfg["T"]):
+        ids_s, u_s = rec["u"][s]
+        M = lib.pg_state(ctx, cfg["P"])["M"]
+        assert M == len(ids_s)
+        buf.u[:M].copy_(torch.from_numpy(u_s.astype(np.float32)))
+        lib.pg_net_forward(ctx, s)                       # network kind NONE: marks u as supplied
+        if s in rec["ovf_masks"]:
+            lib.pg_prune(ctx, s)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(buf.masks.cpu().numpy().view(np.uint64), rec["ovf_masks"][s])
+            pr = buf.rewards.cpu().numpy()[:M].astype(np.float64)
+            assert np.max(np.abs(pr - rec["proxy"][s][1])) <= 1e-3 * max(1.0, np.std(rec["proxy"][s][1]))
+        lib.pg_step(ctx, s)
+        ids_a, x_a = rec["x_after"][s]
+        st = lib.pg_state(ctx, cfg["P"])
+        got = buf.x[st["cur_x"]].cpu().numpy()[:st["M"]].astype(np.float64)
+        assert np.max(np.abs(got - x_a)) <= 2e-5 * np.max(np.abs(x_a)), s
+    lib.pg_advantages(ctx)
+    lib.pg_check(ctx)
+    _compare_final(lib, ctx, buf, cfg, rec, x_tol=2e-5, lp_rtol=2e-5)
+    M = lib.pg_state(ctx, cfg["P"])["M"]
+    adv = buf.adv.cpu().numpy()[:M].astype(np.float64)
+    np.testing.assert_allclose(adv, rec["adv"], rtol=2e-3, atol=2e-3)
+    lib.pg_destroy(ctx)
+
+
+def test_loop_call_order_is_enforced(lib):
+    cfg = workloads.get_config("cfg1")
+    c, keep = lib.make_config(cfg, net=False)
+    ctx = lib.pg_create(c)
+    buf = lib.Buffers(ctx, cfg)
+    with pytest.raises(lib.PgError):
+        lib.pg_init_group(ctx, 1)                        # not bound yet
+    lib.pg_bind(ctx, buf)
+    with pytest.raises(lib.PgError):
+        lib.pg_step(ctx, 0)                              # not initialised
+    lib.pg_init_group(ctx, 1)
+    with pytest.raises(lib.PgError) as e:
+        lib.pg_step(ctx, 0)                              # no network evaluation yet
+    assert e.value.status == lib.PG_ESCHED
+    lib.pg_net_forward(ctx, 0)
+    with pytest.raises(lib.PgError):
+        lib.pg_prune(ctx, 0)                             # step 0 is not a checkpoint
+    lib.pg_step(ctx, 0)
+    for s in range(1, 5):
+        lib.pg_net_forward(ctx, s)
+        if s == 4:
+            lib.pg_prune(ctx, 4)
+            with pytest.raises(lib.PgError):
+                lib.pg_net_forward(ctx, 5)               # the prune must be consumed by its step first
+            with pytest.raises(lib.PgError):
+                lib.pg_advantages(ctx)
+        lib.pg_step(ctx, s)
+    assert lib.pg_state(ctx, 1)["M"] == 4
+    with pytest.raises(lib.PgError):
+        lib.pg_prune_forced(ctx, 5, [0b10000])           # u is stale
+    lib.pg_net_forward(ctx, 5)
+    with pytest.raises(lib.PgError):
+        lib.pg_prune_forced(ctx, 5, [0b10000])           # names a slot beyond the 4 members
+    with pytest.raises(lib.PgError):
+        lib.pg_prune_forced(ctx, 5, [0])                 # empty
+    lib.pg_check(ctx)
+    small = lib.Buffers(ctx, cfg)
+    small.c.workspace_bytes = 16
+    with pytest.raises(lib.PgError) as e:
+        lib.pg_bind(ctx, small)
+    assert e.value.status == lib.PG_EWORKSPACE
+    lib.pg_destroy(ctx)
+
+
+def test_nan_reward_is_reported(lib):
+    cfg = workloads.get_config("cfg1")
+    c, keep = lib.make_config(cfg, net=False)
+    ctx = lib.pg_create(c)
+    inp = dict(probe_w=np.ones(cfg["d"], np.float32))
+    buf = lib.Buffers(ctx, cfg, inputs=inp)
+    lib.pg_bind(ctx, buf)
+    lib.pg_init_group(ctx, 3)
+    for s in range(5):
+        buf.u.zero_()
+        if s == 4:
+            buf.u[2, 7] = float("nan")
+        lib.pg_net_forward(ctx, s)
+        if s == 4:
+            lib.pg_prune(ctx, s)
+        lib.pg_step(ctx, s)
+    with pytest.raises(lib.PgError) as e:
+        lib.pg_check(ctx)
+    assert e.value.status == lib.PG_ENAN
+    assert lib.pg_state(ctx, 1)["M"] == 4                # the loop itself stayed in bounds
+    lib.pg_destroy(ctx)
