@@ -41,7 +41,7 @@ def run(cfg, tables, inputs, seed, wts=None, net=None, forced_masks=None, eps=1e
     logp_hist = np.full((T, M0), np.nan)
     logp_sum = np.zeros(M0)
     rec = dict(proxy={}, ovf_masks={}, used_masks={}, ovf_j={}, u={}, x_after={},
-               evals=0, updates=0, active=[])
+               evals=0, updates=0, active=[], x_init=x.copy())
     sched = [dict(cfg["schedule"][g]) for g in range(P)]
 
     for s in range(T):
