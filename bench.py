@@ -1,0 +1,136 @@
+"""Benchmark of the Pro-GRPO pruned-sampling hot path on one MI355X.
+
+One "step" = one whole pass of the hot path over one batch: init group, T x (network evaluation on
+every active trajectory, prune at the checkpoints, fused update + log-prob), final rewards and
+advantages.  Metric: trajectory-steps/s (network evaluations of one trajectory at one step) and
+seconds per group.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+DESCRIPTIONS = {
+    "cfg1": "tiny flow group 8->4, DiT 64 tok x 128 x 2 blocks",
+    "cfg2": "diffusion-shaped group N=24->12 @ step 5 of 20 (DDIM eta=1), latent 4x64x64, DiT 1024 tok x 768 x 12 blocks, 77x768 cross-attention",
+    "cfg3": "flow-shaped group N=48->32->16 @ steps 2,4 of 10, latent 16x64x64, DiT (1024+154) tok x 1536 x 24 blocks, joint attention",
+    "cfg4": "8 prompts x N=48 (ragged 48->32->16, one group unpruned), cfg3 network, one packed batch",
+}
+
+
+def cpu_baseline(cfg, w, inp, seed, budget_traj):
+    """The oracle, as it stands, on a bounded sample: `budget_traj` trajectories of the first group for
+    one whole step (network evaluation, preview + proxy reward, OVF over the sample, update + log-prob)."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import dit, philox, sampler, ovf
+    s = cfg["sampler"]
+    tables = (sampler.flow_sde_tables(cfg["T"], s["a"]) if s["kind"] == "flow"
+              else sampler.ddim_sde_tables(cfg["T"], s["eta"], s["beta0"], s["beta1"], s["T_train"]))
+    n, d = budget_traj, cfg["d"]
+    t0 = time.perf_counter()
+    x = np.stack([philox.normals(seed, philox.STREAM_INIT, i, 0, d) for i in range(n)])
+    ctx = inp["ctx"][0] if inp.get("ctx") is not None else None
+    u = dit.forward(w, cfg, x, tables["t_in"][0], inp["y"][0], ctx)
+    r = sampler.linear_reward(sampler.preview(x, u, tables["P"][0], tables["Q"][0]), inp["probe_w"], inp["probe_b"])
+    ovf.ovf_select(r.astype(np.float32), max(1, n // 2))
+    xi = np.stack([philox.normals(seed, philox.STREAM_STEP, i, 0, d) for i in range(n)])
+    xn, mean = sampler.sde_step(x, u, tables["A"][0], tables["B"][0], tables["C"][0], xi)
+    sampler.gaussian_logprob(xn, mean, tables["C"][0])
+    dt = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return dict(value=n / dt, unit="trajectory-steps/s", cores=int(threads), kind="oracle",
+                sample=f"{n} trajectories of group 0, one full step (network + preview/OVF + update/log-prob) in {dt:.1f} s",
+                s_per_group=workloads_evals(cfg) / (n / dt) / cfg["P"])
+
+
+def workloads_evals(cfg):
+    from paper_2512_15347_amd import workloads
+    return workloads.network_evals(cfg)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg2", choices=sorted(DESCRIPTIONS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=0, help="trajectories in the oracle sample (0 = auto)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("this build runs on ONE GPU: the path has no inter-GPU part (groups are independent and would "
+                 "shard by prompt); run with --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2512_15347_amd import binding as pg, workloads
+
+    cfg = workloads.get_config(args.workload)
+    seed = workloads.MASTER_SEED
+    w = workloads.make_weights(cfg)
+    inp = workloads.make_inputs(cfg, w)
+    c, keep = pg.make_config(cfg, probe_bias=inp["probe_b"])
+    ctx = pg.pg_create(c)
+    buf = pg.Buffers(ctx, cfg, inputs=inp, weights_flat=pg.pack_weights(ctx, cfg, w))
+    pg.pg_bind(ctx, buf)
+    evals = workloads.network_evals(cfg)
+
+    for i in range(args.warmup):
+        pg.pg_sample_group(ctx, seed + i)
+    pg.pg_check(ctx)
+    torch.cuda.synchronize()
+
+    pg.pg_profile_begin(1 << 18)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        pg.pg_sample_group(ctx, seed + 100 + i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = {k: pg.pg_profile_read(i) for i, k in enumerate(("gemm", "attention", "sde_step", "preview"))}
+    pg.pg_profile_end()
+    pg.pg_check(ctx)
+    st = pg.pg_state(ctx, cfg["P"])
+    assert st["evals"] == evals, (st, evals)
+
+    g = prof["gemm"]
+    gemm_tflops = g["work"] / (g["ms"] * 1e-3) / 1e12 if g["ms"] > 0 else 0.0
+    a = prof["attention"]
+    s = prof["sde_step"]
+    roofline = dict(bound="mfma", kernel="gemm_kernel (bf16 MFMA GEMM, all epilogues)", achieved=round(gemm_tflops, 2),
+                    peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=round(gemm_tflops / PEAK_BF16_TFLOPS, 4), traffic=None,
+                    launches=g["launches"], avg_launch_us=round(1e3 * g["ms"] / max(g["launches"], 1), 2),
+                    share_of_step_time=round(g["ms"] * 1e-3 / dt, 4))
+    others = dict(
+        attention=dict(tflops=round(a["work"] / (a["ms"] * 1e-3) / 1e12, 2) if a["ms"] > 0 else None,
+                       share_of_step_time=round(a["ms"] * 1e-3 / dt, 4), launches=a["launches"]),
+        sde_step=dict(gbs=round(s["work"] / (s["ms"] * 1e-3) / 1e9, 1) if s["ms"] > 0 else None,
+                      frac_of_hbm_peak=round(s["work"] / (s["ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) if s["ms"] > 0 else None,
+                      share_of_step_time=round(s["ms"] * 1e-3 / dt, 4), launches=s["launches"]))
+
+    out = dict(metric="trajectory-steps/s and s per group (N->k pruned sampling), 1 GPU",
+               value=round(evals * args.steps / dt, 3), unit="trajectory-steps/s", n_gpus=1, steps=args.steps,
+               warmup=args.warmup, ms_per_step=round(1e3 * dt / args.steps, 3),
+               s_per_group=round(dt / args.steps / cfg["P"], 6), higher_is_better=True, scaling="weak",
+               vs_baseline=None, dtype="bf16", data="synthetic",
+               config=dict(workload=f"{args.workload}: {DESCRIPTIONS[args.workload]}",
+                           trajectory_steps_per_group_batch=evals, groups=cfg["P"]),
+               roofline=roofline, other_kernels=others)
+    if not args.no_cpu_baseline:
+        budget = args.cpu_sample or {"cfg1": 8, "cfg2": 8, "cfg3": 1, "cfg4": 1}[args.workload]
+        out["cpu_baseline"] = cpu_baseline(cfg, w, inp, seed, budget)
+    pg.pg_destroy(ctx)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

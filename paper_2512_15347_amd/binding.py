@@ -89,6 +89,9 @@ _SIGNATURES = {
     "pg_group_advantages": (_i32, [_vp, _vp, _i32, _f64, _vp, _vp]),
     "pg_gemm_bf16": (_i32, [_vp, _i64, _vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _vp]),
     "pg_attention_bf16": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp]),
+    "pg_profile_begin": (_i32, [_i32]),
+    "pg_profile_read": (_i32, [_i32, _dp, _dp, C.POINTER(_i64)]),
+    "pg_profile_end": (_i32, []),
 }
 EXPORTS = sorted(_SIGNATURES)
 for _name, (_res, _args) in _SIGNATURES.items():
@@ -352,3 +355,17 @@ def pg_gemm_bf16(A, lda, W, ldw, bias, Cout, ldc, M, N, K, stream=None):
 
 def pg_attention_bf16(q, k, vt, out, B, Lq, Lk, heads, hd, stream=None):
     _check(_lib.pg_attention_bf16(_ptr(q), _ptr(k), _ptr(vt), _ptr(out), B, Lq, Lk, heads, hd, _stream(stream)))
+
+
+def pg_profile_begin(max_records=1 << 16):
+    _check(_lib.pg_profile_begin(max_records))
+
+
+def pg_profile_read(kind):
+    ms, work, n = C.c_double(), C.c_double(), _i64()
+    _check(_lib.pg_profile_read(kind, C.byref(ms), C.byref(work), C.byref(n)))
+    return dict(ms=ms.value, work=work.value, launches=n.value)
+
+
+def pg_profile_end():
+    _check(_lib.pg_profile_end())

@@ -18,6 +18,26 @@ pg_status fail(pg_status st, const char* fmt, ...) {
   return st;
 }
 
+struct ProfRec { int kind; double work; hipEvent_t a, b; bool closed; };
+static std::vector<ProfRec> g_prof;
+static bool g_prof_on = false;
+static size_t g_prof_cap = 0;
+
+int prof_open(int kind, double work, hipStream_t s) {
+  if (!g_prof_on || g_prof.size() >= g_prof_cap) return -1;
+  ProfRec r{kind, work, nullptr, nullptr, false};
+  if (hipEventCreate(&r.a) != hipSuccess) return -1;
+  if (hipEventCreate(&r.b) != hipSuccess) { (void)hipEventDestroy(r.a); return -1; }
+  (void)hipEventRecord(r.a, s);
+  g_prof.push_back(r);
+  return (int)g_prof.size() - 1;
+}
+void prof_close(int rec, hipStream_t s) {
+  if (rec < 0 || rec >= (int)g_prof.size()) return;
+  (void)hipEventRecord(g_prof[rec].b, s);
+  g_prof[rec].closed = true;
+}
+
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 // ---- per-step scalars of x' = A x + B u + C xi and x_hat = P x + Q u ----
@@ -153,6 +173,41 @@ static pg_status plan_workspace(pg_ctx* c) {
 using namespace pg;
 
 extern "C" const char* pg_last_error(void) { return error_buffer(); }
+
+extern "C" pg_status pg_profile_begin(int32_t max_records) {
+  if (max_records < 1) return fail(PG_EINVAL, "pg_profile_begin: max_records = %d", max_records);
+  for (auto& r : g_prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  g_prof.clear();
+  g_prof.reserve(max_records);
+  g_prof_cap = (size_t)max_records;
+  g_prof_on = true;
+  return PG_OK;
+}
+
+extern "C" pg_status pg_profile_read(int32_t kind, double* total_ms, double* total_work, int64_t* launches) {
+  if (kind < 0 || kind >= PROF_KINDS) return fail(PG_EINVAL, "pg_profile_read: kind %d", kind);
+  double ms = 0.0, work = 0.0;
+  int64_t n = 0;
+  for (auto& r : g_prof) {
+    if (r.kind != kind || !r.closed) continue;
+    PG_HIP(hipEventSynchronize(r.b));
+    float t = 0.f;
+    PG_HIP(hipEventElapsedTime(&t, r.a, r.b));
+    ms += t; work += r.work; ++n;
+  }
+  if (total_ms) *total_ms = ms;
+  if (total_work) *total_work = work;
+  if (launches) *launches = n;
+  return PG_OK;
+}
+
+extern "C" pg_status pg_profile_end(void) {
+  g_prof_on = false;
+  for (auto& r : g_prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  g_prof.clear();
+  g_prof_cap = 0;
+  return PG_OK;
+}
 
 extern "C" pg_status pg_create(const pg_config* cfg, pg_ctx** out) {
   if (out) *out = nullptr;

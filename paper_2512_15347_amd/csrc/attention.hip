@@ -202,8 +202,10 @@ pg_status launch_attention(const AttnArgs& a, int hd, hipStream_t s) {
     return fail(PG_ESHAPE, "attention: operands need 16-byte aligned rows");
   if (a.heads > 65535 || a.B > 65535) return fail(PG_ESHAPE, "attention: grid limit");
   const dim3 grid((a.Lq + QTILE - 1) / QTILE, a.heads, a.B);
+  const int rec = prof_open(PROF_ATTENTION, 4.0 * a.B * (double)a.heads * a.Lq * (double)a.Lk * hd, s);
   if (hd == 64) attention_kernel<64><<<grid, dim3(ATT_THREADS), 0, s>>>(a);
   else attention_kernel<32><<<grid, dim3(ATT_THREADS), 0, s>>>(a);
+  prof_close(rec, s);
   PG_LAUNCH_CHECK("attention_kernel");
   return PG_OK;
 }

@@ -42,4 +42,10 @@ constexpr int STREAM_CHUNK = STREAM_THREADS * STREAM_ITERS * 4;   // floats
 
 inline int64_t chunks_per_traj(int64_t d) { return (d + STREAM_CHUNK - 1) / STREAM_CHUNK; }
 
+// Optional measurement: when switched on (pg_profile_begin) the launches of the heavy kernels are
+// bracketed by HIP events on their own stream; `work` is the algorithmic flop or byte count.
+enum ProfKind { PROF_GEMM = 0, PROF_ATTENTION = 1, PROF_SDE_STEP = 2, PROF_PREVIEW = 3, PROF_KINDS = 4 };
+int prof_open(int kind, double work, hipStream_t s);     // returns a record index or -1 when off
+void prof_close(int rec, hipStream_t s);
+
 }  // namespace pg

@@ -266,7 +266,7 @@ pg_status net_forward(pg_ctx* c, int step, hipStream_t s) {
     PG_LAUNCH_CHECK("patchify_kernel");
     GemmArgs g{};
     g.A = tok; g.lda = Kp; g.W = n.w(PG_W_PE_W); g.ldw = n.ld(PG_W_PE_W); g.bias = n.w(PG_W_PE_B);
-    g.M = Ri; g.N = D; g.K = Kp; g.outf = h; g.ldo = D; g.L = L; g.Li = Li; g.pos = n.w(PG_W_POS);
+    g.M = Ri; g.N = D; g.K = Kp; g.k_algo = 4 * f.C; g.outf = h; g.ldo = D; g.L = L; g.Li = Li; g.pos = n.w(PG_W_POS);
     PG_TRY(launch_gemm(g, EPI_EMBED, s));
   }
   if (f.net_kind == PG_NET_JOINT) {

@@ -55,6 +55,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
   const int tn = (b % band) / gsz;
   const int m0 = tm * BM, n0 = tn * BN;
 
+  // value-channel tiles of the QKV projection are computed transposed (operands swapped) so that
+  // V^T can be stored with consecutive lanes on consecutive tokens
+  const bool tr = (EPI == EPI_QKV) && (n0 >= a.v_start);
+
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 2, wn = wave & 3;
   const int l32 = lane & 31, half = lane >> 5;
@@ -101,8 +105,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
   __syncthreads();
 
   for (int kt = 0; kt < nk; ++kt) {
-    const unsigned char* sA = smem + (kt & 1) * STAGE_BYTES;
-    const unsigned char* sW = sA + TILE_BYTES;
+    const unsigned char* sA = smem + (kt & 1) * STAGE_BYTES + (tr ? TILE_BYTES : 0);   // first MFMA operand
+    const unsigned char* sW = smem + (kt & 1) * STAGE_BYTES + (tr ? 0 : TILE_BYTES);   // second MFMA operand
     if (kt + 1 < nk) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -134,26 +138,90 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
     __syncthreads();
   }
 
-  // ---- epilogue: lane holds column n and rows 8*(e/4) + 4*half + e%4 of each 32x32 tile ----
+  // ---- epilogue: in each 32x32 tile a lane holds ONE column (l32) and rows 8q + 4*half + t ----
+  if (EPI == EPI_QKV && tr) {
+    // transposed tile: accumulator rows are output columns n (value channels), its columns are tokens,
+    // so consecutive lanes write consecutive tokens of one row of V^T
+    const int Dv = a.N - a.v_start;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int r = m0 + wn * 64 + j * 32 + l32;
+      if (r >= a.M) continue;
+      const int traj = r / a.L, tok = r - traj * a.L;
+      uint16_t* vcol = a.vt + (int64_t)traj * Dv * a.Lpad + tok;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const int n = n0 + wm * 128 + i * 32 + 8 * q + 4 * half + t;
+            if (n < a.N) {
+              const float bv = a.bias ? bf16_to_f32(a.bias[n]) : 0.f;
+              vcol[(int64_t)(n - a.v_start) * a.Lpad] = f32_to_bf16(acc[i][j][4 * q + t] + bv);
+            }
+          }
+    }
+    return;
+  }
+  int n_j[2];
+  float bias_j[2];
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
-    const int n = n0 + wn * 64 + j * 32 + l32;
-    if (n >= a.N) continue;
-    const float bias = a.bias ? bf16_to_f32(a.bias[n]) : 0.f;
+    n_j[j] = n0 + wn * 64 + j * 32 + l32;
+    bias_j[j] = (a.bias && n_j[j] < a.N) ? bf16_to_f32(a.bias[n_j[j]]) : 0.f;
+  }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < 4; ++i) {
+    const int rb = m0 + wm * 128 + i * 32 + 4 * half;       // rows rb + 8q + t
+    if (EPI == EPI_RESID) {
+      // phase 1: every load of this 32-row slab (old h, gates) is issued before the first store,
+      // so the memory latencies overlap instead of chaining through possible aliasing
+      float hv[4][2][4], gv[4][2][4];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int r0 = m0 + wm * 128 + i * 32 + 8 * q + 4 * half;
-        if (r0 >= a.M) continue;
-        int traj = 0, tok = 0;
-        if (EPI == EPI_EMBED || EPI == EPI_UNPATCH) { traj = r0 / a.Li; tok = r0 - traj * a.Li; }
-        if (EPI == EPI_QKV || EPI == EPI_RESID) { traj = r0 / a.L; tok = r0 - traj * a.L; }
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int r = rb + 8 * q + t;
+          const bool ok = r < a.M;
+          int gid = 0;
+          if (a.gate && ok) gid = a.group_of[r / a.L];
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            const bool okn = ok && n_j[j] < a.N;
+            hv[q][j][t] = okn ? a.outf[(int64_t)r * a.ldo + n_j[j]] : 0.f;
+            gv[q][j][t] = (a.gate && okn) ? a.gate[(int64_t)gid * a.gate_ld + n_j[j]] : 1.0f;
+          }
+        }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int r = rb + 8 * q + t;
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            if (r < a.M && n_j[j] < a.N)
+              a.outf[(int64_t)r * a.ldo + n_j[j]] = hv[q][j][t] + gv[q][j][t] * (acc[i][j][4 * q + t] + bias_j[j]);
+        }
+      continue;
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int r0 = rb + 8 * q;
+      if (r0 >= a.M) continue;
+      int traj0 = 0, tok0 = 0;
+      if (EPI == EPI_EMBED || EPI == EPI_UNPATCH) { traj0 = r0 / a.Li; tok0 = r0 - traj0 * a.Li; }
+      if (EPI == EPI_QKV) { traj0 = r0 / a.L; tok0 = r0 - traj0 * a.L; }
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int n = n_j[j];
+        if (n >= a.N) continue;
+        int traj = traj0, tok = tok0;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           const int r = r0 + t;
           if (r >= a.M) break;
-          const float v = acc[i][j][4 * q + t] + bias;
+          const float v = acc[i][j][4 * q + t] + bias_j[j];
           if (EPI == EPI_F32) {
             a.outf[(int64_t)r * a.ldo + n] = v;
           } else if (EPI == EPI_EMBED) {
@@ -169,12 +237,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
             ++tok;
           } else if (EPI == EPI_GELU) {
             a.outb[(int64_t)r * a.ldob + n] = f32_to_bf16(gelu_tanh(v));
-          } else if (EPI == EPI_RESID) {
-            if (tok >= a.L) { tok -= a.L; ++traj; }
-            const float g = a.gate ? a.gate[(int64_t)a.group_of[traj] * a.gate_ld + n] : 1.0f;
-            float* dst = a.outf + (int64_t)r * a.ldo + n;
-            *dst = *dst + g * v;
-            ++tok;
           } else if (EPI == EPI_UNPATCH) {
             if (tok >= a.Li) { tok -= a.Li; ++traj; }
             const int py = tok / a.Wp, px = tok - py * a.Wp;
@@ -209,16 +271,20 @@ pg_status launch_gemm(const GemmArgs& a, int epilogue, hipStream_t s) {
   if (a.lda % 8 || a.ldw % 8 || a.lda < a.K || a.ldw < a.K || ((uintptr_t)a.A & 15) || ((uintptr_t)a.W & 15))
     return fail(PG_ESHAPE, "GEMM operands need 16-byte aligned rows (lda %lld, ldw %lld)", (long long)a.lda, (long long)a.ldw);
   if (!a.A || !a.W) return fail(PG_EINVAL, "GEMM: null operand");
+  const int rec = prof_open(PROF_GEMM, 2.0 * a.M * (double)a.N * (a.k_algo > 0 ? a.k_algo : a.K), s);
+  pg_status st = PG_EINVAL;
   switch (epilogue) {
-    case EPI_F32: return launch_one<EPI_F32>(a, s);
-    case EPI_EMBED: return launch_one<EPI_EMBED>(a, s);
-    case EPI_BF16: return launch_one<EPI_BF16>(a, s);
-    case EPI_QKV: return launch_one<EPI_QKV>(a, s);
-    case EPI_GELU: return launch_one<EPI_GELU>(a, s);
-    case EPI_RESID: return launch_one<EPI_RESID>(a, s);
-    case EPI_UNPATCH: return launch_one<EPI_UNPATCH>(a, s);
+    case EPI_F32: st = launch_one<EPI_F32>(a, s); break;
+    case EPI_EMBED: st = launch_one<EPI_EMBED>(a, s); break;
+    case EPI_BF16: st = launch_one<EPI_BF16>(a, s); break;
+    case EPI_QKV: st = launch_one<EPI_QKV>(a, s); break;
+    case EPI_GELU: st = launch_one<EPI_GELU>(a, s); break;
+    case EPI_RESID: st = launch_one<EPI_RESID>(a, s); break;
+    case EPI_UNPATCH: st = launch_one<EPI_UNPATCH>(a, s); break;
+    default: st = fail(PG_EINVAL, "unknown GEMM epilogue %d", epilogue);
   }
-  return fail(PG_EINVAL, "unknown GEMM epilogue %d", epilogue);
+  prof_close(rec, s);
+  return st;
 }
 
 }  // namespace pg

@@ -19,6 +19,7 @@ struct GemmArgs {
   const uint16_t* W; int64_t ldw;
   const uint16_t* bias;            // bf16 [N] or NULL
   int M, N, K;
+  int k_algo;                      // unpadded K for flop accounting (0: same as K)
   float* outf; int64_t ldo;
   uint16_t* outb; int64_t ldob;
   // epilogue extras

@@ -196,9 +196,11 @@ extern "C" pg_status pg_sde_step_logprob(const float* x, const float* u, float* 
   if (x_out == x) return fail(PG_EINVAL, "pg_sde_step_logprob: x_out must not alias x");
   if (!(C > 0.0)) return fail(PG_EINVAL, "pg_sde_step_logprob: noise scale C = %g must be > 0", C);
   const int chunks = (int)chunks_per_traj(d);
+  const int rec = prof_open(PROF_SDE_STEP, 12.0 * (double)n_traj * (double)d, (hipStream_t)stream);
   sde_step_kernel<<<dim3((unsigned)(n_traj * chunks)), dim3(STREAM_THREADS), 0, (hipStream_t)stream>>>(
       x, u, x_out, src, orig_id, (int)(d / 4), chunks, (float)A, (float)B, (float)C, (uint32_t)seed,
       (uint32_t)(seed >> 32), step, partials);
+  prof_close(rec, (hipStream_t)stream);
   PG_LAUNCH_CHECK("sde_step_kernel");
   const double log_norm = (double)d * (log(C) + 0.5 * log(2.0 * M_PI));
   logprob_finish_kernel<<<dim3((unsigned)((n_traj + 127) / 128)), dim3(128), 0, (hipStream_t)stream>>>(
@@ -216,12 +218,14 @@ extern "C" pg_status pg_preview_reward(const float* x, const float* u, const flo
   if (!u && Qc != 0.0) return fail(PG_EINVAL, "pg_preview_reward: u is NULL but Qc = %g", Qc);
   const int chunks = (int)chunks_per_traj(d);
   const dim3 grid((unsigned)(n_traj * chunks)), block(STREAM_THREADS);
+  const int rec = prof_open(PROF_PREVIEW, ((u && Qc != 0.0) ? 8.0 : 4.0) * (double)n_traj * (double)d, (hipStream_t)stream);
   if (u && Qc != 0.0)
     preview_reward_kernel<true><<<grid, block, 0, (hipStream_t)stream>>>(x, u, w, (int)(d / 4), chunks,
                                                                           (float)Pc, (float)Qc, partials);
   else
     preview_reward_kernel<false><<<grid, block, 0, (hipStream_t)stream>>>(x, x, w, (int)(d / 4), chunks,
                                                                            (float)Pc, 0.f, partials);
+  prof_close(rec, (hipStream_t)stream);
   PG_LAUNCH_CHECK("preview_reward_kernel");
   reward_finish_kernel<<<dim3((unsigned)((n_traj + 127) / 128)), dim3(128), 0, (hipStream_t)stream>>>(
       partials, chunks, (int)n_traj, bias, rewards);
