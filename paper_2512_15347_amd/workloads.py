@@ -152,3 +152,12 @@ def stress_latents(n_traj, d, seed=MASTER_SEED):
     x = rng.standard_normal((n_traj, d), dtype=np.float32)
     u = rng.standard_normal((n_traj, d), dtype=np.float32)
     return x, u
+
+
+def stress_latent_rows(rows, d, seed=MASTER_SEED, stream=4100):
+    """Rows of the large fused-update stress tensor, each drawn from its own seed so that any
+    sample of rows can be regenerated without the rest: fp32 ~ N(0, 1)."""
+    out = np.empty((len(rows), d), dtype=np.float32)
+    for i, r in enumerate(rows):
+        out[i] = np.random.default_rng([seed, stream, int(r)]).standard_normal(d, dtype=np.float32)
+    return out
