@@ -100,8 +100,11 @@ __global__ void patchify_kernel(const float* __restrict__ x, uint16_t* __restric
   dst[1] = hi;
 }
 
-// out[r', :] = bf16(LN(h[r, :]) * (1 + scale[g]) + shift[g]); one wave per row, three cached passes.
+// out[r', :] = bf16(LN(h[r, :]) * (1 + scale[g]) + shift[g]); one wave per row.  The row lives in
+// registers (NV float4 per lane, D = 256 * NV) so h is read once; NV = 0 is the generic route for
+// widths that are not a multiple of 256 (three cached passes).
 // Rows: r' = m * L_out + t for t < L_out reads h row m * L_in + t (L_out < L_in drops the context rows).
+template <int NV>
 __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restrict__ h, uint16_t* __restrict__ out,
                                                           const float* __restrict__ shift,
                                                           const float* __restrict__ scale, int64_t mod_ld,
@@ -112,17 +115,53 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restric
   if (ro >= rows_out) return;
   const int m = ro / L_out, t = ro - m * L_out;
   const float* hr = h + ((int64_t)m * L_in + t) * D;
+  uint16_t* orow = out + (int64_t)ro * D;
+  const float* sh = nullptr;
+  const float* sc = nullptr;
+  if (shift) {
+    const int g = group_of[m];
+    sh = shift + (int64_t)g * mod_ld;
+    sc = scale + (int64_t)g * mod_ld;
+  }
+  if (NV > 0) {
+    float4 v[NV > 0 ? NV : 1];
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      v[i] = reinterpret_cast<const float4*>(hr)[lane + 64 * i];
+      s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    }
+    const float mu = wave_allsum(s) / (float)D;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      v[i].x -= mu; v[i].y -= mu; v[i].z -= mu; v[i].w -= mu;
+      q += (v[i].x * v[i].x + v[i].y * v[i].y) + (v[i].z * v[i].z + v[i].w * v[i].w);
+    }
+    const float rstd = rsqrtf(wave_allsum(q) / (float)D + 1e-6f);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      float4 o = {v[i].x * rstd, v[i].y * rstd, v[i].z * rstd, v[i].w * rstd};
+      if (sh) {
+        const float4 a = reinterpret_cast<const float4*>(sc)[lane + 64 * i];
+        const float4 b = reinterpret_cast<const float4*>(sh)[lane + 64 * i];
+        o.x = o.x * (1.0f + a.x) + b.x; o.y = o.y * (1.0f + a.y) + b.y;
+        o.z = o.z * (1.0f + a.z) + b.z; o.w = o.w * (1.0f + a.w) + b.w;
+      }
+      uint2 pk;
+      pk.x = (uint32_t)f2bf(o.x) | ((uint32_t)f2bf(o.y) << 16);
+      pk.y = (uint32_t)f2bf(o.z) | ((uint32_t)f2bf(o.w) << 16);
+      reinterpret_cast<uint2*>(orow)[lane + 64 * i] = pk;
+    }
+    return;
+  }
   float s = 0.f;
   for (int k = lane; k < D; k += WAVE) s += hr[k];
   const float mu = wave_allsum(s) / (float)D;
   float q = 0.f;
   for (int k = lane; k < D; k += WAVE) { const float dv = hr[k] - mu; q += dv * dv; }
   const float rstd = rsqrtf(wave_allsum(q) / (float)D + 1e-6f);
-  uint16_t* orow = out + (int64_t)ro * D;
-  if (shift) {
-    const int g = group_of[m];
-    const float* sh = shift + (int64_t)g * mod_ld;
-    const float* sc = scale + (int64_t)g * mod_ld;
+  if (sh) {
     for (int k = lane; k < D; k += WAVE) orow[k] = f2bf((hr[k] - mu) * rstd * (1.0f + sc[k]) + sh[k]);
   } else {
     for (int k = lane; k < D; k += WAVE) orow[k] = f2bf((hr[k] - mu) * rstd);
@@ -277,8 +316,12 @@ pg_status net_forward(pg_ctx* c, int step, hipStream_t s) {
   }
 
   auto layer_norm = [&](const float* shift, const float* scale, int64_t ld, int rows_out, int L_out) -> pg_status {
-    ln_modulate_kernel<<<dim3((rows_out + 3) / 4), dim3(256), 0, s>>>(h, act, shift, scale, ld, group_of, rows_out, L,
-                                                                      L_out, D);
+    const dim3 grid((rows_out + 3) / 4), block(256);
+    if (D == 768) ln_modulate_kernel<3><<<grid, block, 0, s>>>(h, act, shift, scale, ld, group_of, rows_out, L, L_out, D);
+    else if (D == 1536) ln_modulate_kernel<6><<<grid, block, 0, s>>>(h, act, shift, scale, ld, group_of, rows_out, L, L_out, D);
+    else if (D == 1024) ln_modulate_kernel<4><<<grid, block, 0, s>>>(h, act, shift, scale, ld, group_of, rows_out, L, L_out, D);
+    else if (D == 256) ln_modulate_kernel<1><<<grid, block, 0, s>>>(h, act, shift, scale, ld, group_of, rows_out, L, L_out, D);
+    else ln_modulate_kernel<0><<<grid, block, 0, s>>>(h, act, shift, scale, ld, group_of, rows_out, L, L_out, D);
     PG_LAUNCH_CHECK("ln_modulate_kernel");
     return PG_OK;
   };

@@ -1,12 +1,16 @@
 // bf16 MFMA GEMM for gfx950: C[M, N] = A[M, K] W[N, K]^T with a fused epilogue.  This is where the
 // network evaluation of every denoising step spends its time (the noise-prediction row of the paper's
-// cost table, Sec. 6.2), so the tile is sized for the 160 KB LDS and the 32x32x16 bf16 MFMA:
-//   workgroup tile 256 x 256 x 64, 8 wavefronts as 2 (M) x 4 (N), each owning 128 x 64 = 4 x 2 MFMA tiles;
-//   both operands are K-contiguous, staged global -> registers -> LDS in 16-byte chunks, two LDS stages
-//   (2 x 64 KB), one barrier per K step; chunk positions are XOR-swizzled so that both the 16-byte
-//   staging writes and the 16-byte MFMA operand reads are bank-conflict free;
+// cost table, Sec. 6.2).  Built around the 32x32x16 bf16 MFMA:
+//   both operands are K-contiguous and staged global -> registers -> LDS in 16-byte chunks with two LDS
+//   stages; the loads of tile kt+2 are in flight while tile kt is multiplied and tile kt+1 is written
+//   to LDS at the top of the iteration, one barrier per K step; chunk positions are XOR-swizzled so
+//   that both the 16-byte staging writes and the 16-byte MFMA operand reads are bank-conflict free;
 //   workgroup ids are spread so that the tiles resident on one XCD (one L2) form a compact block of
 //   the output and share operand panels.
+// Several tile shapes are instantiated (workgroup tile BM x BN x BK, WM x WN wavefronts); the launcher
+// picks one from the number of output tiles relative to the 256 compute units.
+#include <cmath>
+#include <cstdlib>
 #include "gemm.hpp"
 
 namespace pg {
@@ -15,17 +19,14 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
 
-constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int GEMM_THREADS = 512;
-constexpr int TILE_BYTES = BM * BK * 2;            // one operand tile, 32 KB
-constexpr int STAGE_BYTES = 2 * TILE_BYTES;        // A + W
-constexpr int GEMM_LDS = 2 * STAGE_BYTES;          // 128 KB
 constexpr int GROUP_M = 8;                         // tile rows per raster band
 constexpr int XCDS = 8;
 
-// byte offset of 16-byte chunk `chunk` (0..7) of tile row `row` inside an operand tile
+// byte offset of 16-byte chunk `chunk` of tile row `row` inside an operand tile with CH chunks per row
+template <int CH>
 __device__ __forceinline__ int lds_off(int row, int chunk) {
-  return (row * 8 + (chunk ^ ((row ^ (row >> 3)) & 7))) * 16;
+  if (CH == 8) return (row * 8 + (chunk ^ ((row ^ (row >> 3)) & 7))) * 16;
+  return (row * 4 + (chunk ^ (((row >> 1) ^ (row >> 3)) & 3))) * 16;
 }
 
 __device__ __forceinline__ float gelu_tanh(float x) {
@@ -39,8 +40,15 @@ __device__ __forceinline__ float gelu_tanh(float x) {
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __builtin_bit_cast(float, (uint32_t)b << 16); }
 __device__ __forceinline__ uint16_t f32_to_bf16(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
 
-template <int EPI>
-__global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
+template <int EPI, int BM, int BN, int BK, int WM, int WN, int MINW>
+__global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs a) {
+  constexpr int THREADS = 64 * WM * WN;
+  constexpr int CH = BK / 8;                       // 16-byte chunks per tile row
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;   // 32x32 MFMA tiles per wave
+  constexpr int A_BYTES = BM * BK * 2, W_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + W_BYTES;
+  constexpr int A_LD = BM * CH / THREADS, W_LD = BN * CH / THREADS;   // chunks staged per lane
+  constexpr bool TR = (EPI == EPI_VT);             // accumulate the transposed 32x32 tiles
+  static_assert(BM * CH % THREADS == 0 && BN * CH % THREADS == 0, "staging must divide evenly");
   extern __shared__ __align__(16) unsigned char smem[];
   // ---- which output tile: XCD-aware, banded raster ----
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
@@ -55,129 +63,123 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
   const int tn = (b % band) / gsz;
   const int m0 = tm * BM, n0 = tn * BN;
 
-  // value-channel tiles of the QKV projection are computed transposed (operands swapped) so that
-  // V^T can be stored with consecutive lanes on consecutive tokens
-  const bool tr = (EPI == EPI_QKV) && (n0 >= a.v_start);
-
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 2, wn = wave & 3;
+  const int wm = wave / WN, wn = wave % WN;
   const int l32 = lane & 31, half = lane >> 5;
 
-  // ---- staging assignment: 4 chunks of A and 4 of W per lane ----
-  const int ld_row = tid >> 3, ld_chunk = tid & 7;
-  const uint16_t* a_ptr[4];
-  const uint16_t* w_ptr[4];
-  int st_off[4];
+  // ---- staging assignment ----
+  const uint16_t* a_ptr[A_LD];
+  const uint16_t* w_ptr[W_LD];
+  int a_st[A_LD], w_st[W_LD];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = ld_row + 64 * i;
-    a_ptr[i] = a.A + (int64_t)min(m0 + row, a.M - 1) * a.lda + ld_chunk * 8;
-    w_ptr[i] = a.W + (int64_t)min(n0 + row, a.N - 1) * a.ldw + ld_chunk * 8;
-    st_off[i] = lds_off(row, ld_chunk);
+  for (int i = 0; i < A_LD; ++i) {
+    const int c = tid + i * THREADS, row = c / CH, ch = c % CH;
+    a_ptr[i] = a.A + (int64_t)min(m0 + row, a.M - 1) * a.lda + ch * 8;
+    a_st[i] = lds_off<CH>(row, ch);
   }
-  // operand read offsets inside a tile for k-slab 0; slab ks adds chunk 2*ks (applied under the XOR)
-  int a_row[4], w_row[2];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) a_row[i] = wm * 128 + i * 32 + l32;
+  for (int i = 0; i < W_LD; ++i) {
+    const int c = tid + i * THREADS, row = c / CH, ch = c % CH;
+    w_ptr[i] = a.W + (int64_t)min(n0 + row, a.N - 1) * a.ldw + ch * 8;
+    w_st[i] = A_BYTES + lds_off<CH>(row, ch);
+  }
+  int a_row[TM], w_row[TN];
 #pragma unroll
-  for (int j = 0; j < 2; ++j) w_row[j] = wn * 64 + j * 32 + l32;
+  for (int i = 0; i < TM; ++i) a_row[i] = wm * (BM / WM) + i * 32 + l32;
+#pragma unroll
+  for (int j = 0; j < TN; ++j) w_row[j] = wn * (BN / WN) + j * 32 + l32;
 
-  f32x16 acc[4][2];
+  f32x16 acc[TM][TN];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  u32x4v ra[4], rw[4];
+  u32x4v ra[A_LD], rw[W_LD];
   const int nk = a.K / BK;
+  auto load_regs = [&](int kt) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    ra[i] = *reinterpret_cast<const u32x4v*>(a_ptr[i]);
-    rw[i] = *reinterpret_cast<const u32x4v*>(w_ptr[i]);
-  }
+    for (int i = 0; i < A_LD; ++i) ra[i] = *reinterpret_cast<const u32x4v*>(a_ptr[i] + kt * BK);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    *reinterpret_cast<u32x4v*>(smem + st_off[i]) = ra[i];
-    *reinterpret_cast<u32x4v*>(smem + TILE_BYTES + st_off[i]) = rw[i];
-  }
+    for (int i = 0; i < W_LD; ++i) rw[i] = *reinterpret_cast<const u32x4v*>(w_ptr[i] + kt * BK);
+  };
+  auto store_regs = [&](int stage) {
+    unsigned char* d = smem + stage * STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) *reinterpret_cast<u32x4v*>(d + a_st[i]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < W_LD; ++i) *reinterpret_cast<u32x4v*>(d + w_st[i]) = rw[i];
+  };
+  load_regs(0);
+  store_regs(0);
+  if (nk > 1) load_regs(1);
   __syncthreads();
 
   for (int kt = 0; kt < nk; ++kt) {
-    const unsigned char* sA = smem + (kt & 1) * STAGE_BYTES + (tr ? TILE_BYTES : 0);   // first MFMA operand
-    const unsigned char* sW = smem + (kt & 1) * STAGE_BYTES + (tr ? 0 : TILE_BYTES);   // second MFMA operand
-    if (kt + 1 < nk) {
+    // registers hold tile kt+1: park it in the other stage (last read before the previous barrier),
+    // then start fetching tile kt+2 so that a whole iteration hides its latency
+    if (kt + 1 < nk) store_regs((kt + 1) & 1);
+    if (kt + 2 < nk) load_regs(kt + 2);
+    const unsigned char* sA = smem + (kt & 1) * STAGE_BYTES;
+    const unsigned char* sW = sA + A_BYTES;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        ra[i] = *reinterpret_cast<const u32x4v*>(a_ptr[i] + (kt + 1) * BK);
-        rw[i] = *reinterpret_cast<const u32x4v*>(w_ptr[i] + (kt + 1) * BK);
-      }
-    }
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 af[TM], wf[TN];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 af[4], wf[2];
+      for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const bf16x8*>(sA + lds_off<CH>(a_row[i], 2 * ks + half));
 #pragma unroll
-      for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const bf16x8*>(sA + lds_off(a_row[i], 2 * ks + half));
+      for (int j = 0; j < TN; ++j) wf[j] = *reinterpret_cast<const bf16x8*>(sW + lds_off<CH>(w_row[j], 2 * ks + half));
 #pragma unroll
-      for (int j = 0; j < 2; ++j) wf[j] = *reinterpret_cast<const bf16x8*>(sW + lds_off(w_row[j], 2 * ks + half));
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], wf[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) {
-      unsigned char* dA = smem + ((kt + 1) & 1) * STAGE_BYTES;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        *reinterpret_cast<u32x4v*>(dA + st_off[i]) = ra[i];
-        *reinterpret_cast<u32x4v*>(dA + TILE_BYTES + st_off[i]) = rw[i];
-      }
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = TR ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], af[i], acc[i][j], 0, 0, 0)
+                         : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], wf[j], acc[i][j], 0, 0, 0);
     }
     __syncthreads();
   }
 
   // ---- epilogue: in each 32x32 tile a lane holds ONE column (l32) and rows 8q + 4*half + t ----
-  if (EPI == EPI_QKV && tr) {
-    // transposed tile: accumulator rows are output columns n (value channels), its columns are tokens,
-    // so consecutive lanes write consecutive tokens of one row of V^T
-    const int Dv = a.N - a.v_start;
+  if (TR) {
+    // transposed tiles: accumulator rows are output columns n (value channels), its columns are tokens,
+    // so consecutive lanes write consecutive tokens of one row of V^T[traj][n][token]
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int r = m0 + wn * 64 + j * 32 + l32;
+    for (int i = 0; i < TM; ++i) {
+      const int r = m0 + wm * (BM / WM) + i * 32 + l32;
       if (r >= a.M) continue;
       const int traj = r / a.L, tok = r - traj * a.L;
-      uint16_t* vcol = a.vt + (int64_t)traj * Dv * a.Lpad + tok;
+      uint16_t* vcol = a.vt + (int64_t)traj * a.N * a.Lpad + tok;
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
         for (int q = 0; q < 4; ++q)
 #pragma unroll
           for (int t = 0; t < 4; ++t) {
-            const int n = n0 + wm * 128 + i * 32 + 8 * q + 4 * half + t;
+            const int n = n0 + wn * (BN / WN) + j * 32 + 8 * q + 4 * half + t;
             if (n < a.N) {
               const float bv = a.bias ? bf16_to_f32(a.bias[n]) : 0.f;
-              vcol[(int64_t)(n - a.v_start) * a.Lpad] = f32_to_bf16(acc[i][j][4 * q + t] + bv);
+              vcol[(int64_t)n * a.Lpad] = f32_to_bf16(acc[i][j][4 * q + t] + bv);
             }
           }
     }
     return;
   }
-  int n_j[2];
-  float bias_j[2];
+  int n_j[TN];
+  float bias_j[TN];
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    n_j[j] = n0 + wn * 64 + j * 32 + l32;
+  for (int j = 0; j < TN; ++j) {
+    n_j[j] = n0 + wn * (BN / WN) + j * 32 + l32;
     bias_j[j] = (a.bias && n_j[j] < a.N) ? bf16_to_f32(a.bias[n_j[j]]) : 0.f;
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int rb = m0 + wm * 128 + i * 32 + 4 * half;       // rows rb + 8q + t
+  for (int i = 0; i < TM; ++i) {
+    const int rb = m0 + wm * (BM / WM) + i * 32 + 4 * half;       // rows rb + 8q + t
     if (EPI == EPI_RESID) {
       // phase 1: every load of this 32-row slab (old h, gates) is issued before the first store,
       // so the memory latencies overlap instead of chaining through possible aliasing
-      float hv[4][2][4], gv[4][2][4];
+      float hv[4][TN][4], gv[4][TN][4];
 #pragma unroll
       for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -187,7 +189,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
           int gid = 0;
           if (a.gate && ok) gid = a.group_of[r / a.L];
 #pragma unroll
-          for (int j = 0; j < 2; ++j) {
+          for (int j = 0; j < TN; ++j) {
             const bool okn = ok && n_j[j] < a.N;
             hv[q][j][t] = okn ? a.outf[(int64_t)r * a.ldo + n_j[j]] : 0.f;
             gv[q][j][t] = (a.gate && okn) ? a.gate[(int64_t)gid * a.gate_ld + n_j[j]] : 1.0f;
@@ -199,7 +201,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
         for (int t = 0; t < 4; ++t) {
           const int r = rb + 8 * q + t;
 #pragma unroll
-          for (int j = 0; j < 2; ++j)
+          for (int j = 0; j < TN; ++j)
             if (r < a.M && n_j[j] < a.N)
               a.outf[(int64_t)r * a.ldo + n_j[j]] = hv[q][j][t] + gv[q][j][t] * (acc[i][j][4 * q + t] + bias_j[j]);
         }
@@ -211,9 +213,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
       if (r0 >= a.M) continue;
       int traj0 = 0, tok0 = 0;
       if (EPI == EPI_EMBED || EPI == EPI_UNPATCH) { traj0 = r0 / a.Li; tok0 = r0 - traj0 * a.Li; }
-      if (EPI == EPI_QKV) { traj0 = r0 / a.L; tok0 = r0 - traj0 * a.L; }
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
+      for (int j = 0; j < TN; ++j) {
         const int n = n_j[j];
         if (n >= a.N) continue;
         int traj = traj0, tok = tok0;
@@ -230,11 +231,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
             ++tok;
           } else if (EPI == EPI_BF16) {
             a.outb[(int64_t)r * a.ldob + n] = f32_to_bf16(v);
-          } else if (EPI == EPI_QKV) {
-            if (tok >= a.L) { tok -= a.L; ++traj; }
-            if (n < a.v_start) a.outb[(int64_t)r * a.ldob + n] = f32_to_bf16(v);
-            else a.vt[((int64_t)traj * (a.N - a.v_start) + (n - a.v_start)) * a.Lpad + tok] = f32_to_bf16(v);
-            ++tok;
           } else if (EPI == EPI_GELU) {
             a.outb[(int64_t)r * a.ldob + n] = f32_to_bf16(gelu_tanh(v));
           } else if (EPI == EPI_UNPATCH) {
@@ -250,34 +246,76 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(const GemmArgs a) {
   }
 }
 
-template <int EPI>
-static pg_status launch_one(const GemmArgs& a, hipStream_t s) {
+template <int EPI, int BM, int BN, int BK, int WM, int WN, int MINW>
+static pg_status launch_tile(const GemmArgs& a, hipStream_t s) {
+  constexpr int LDS = 2 * (BM + BN) * BK * 2;
   static bool attr_set = false;
   if (!attr_set) {
-    PG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel<EPI>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS));
+    PG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel<EPI, BM, BN, BK, WM, WN, MINW>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, LDS));
     attr_set = true;
   }
   const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
   const int grid = (tiles + XCDS - 1) / XCDS * XCDS;
-  gemm_kernel<EPI><<<dim3(grid), dim3(GEMM_THREADS), GEMM_LDS, s>>>(a);
+  gemm_kernel<EPI, BM, BN, BK, WM, WN, MINW><<<dim3(grid), dim3(64 * WM * WN), LDS, s>>>(a);
   PG_LAUNCH_CHECK("gemm_kernel");
   return PG_OK;
 }
 
+// Tile choice.  A launch runs in rounds of 256 concurrent workgroups (one per compute unit); the last
+// round is usually part empty, and with few K steps a tile's fixed prologue / epilogue weighs more.
+// Pick the shape with the best product of slot occupancy and the measured relative speed of its main
+// loop.  PROGRPO_GEMM_TILE (0..3) overrides the heuristic; it is a tuning aid.
+static int pick_tile(const GemmArgs& a) {
+  static const int forced = [] { const char* e = getenv("PROGRPO_GEMM_TILE"); return e ? atoi(e) : -1; }();
+  if (forced >= 0 && forced <= 3) return forced;
+  auto score = [&](int bm, int bn, int per_cu, double speed) {
+    const double tiles = (double)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn);
+    const double slots = 256.0 * per_cu;
+    const double useful = (double)a.M * a.N / ((double)bm * bn);      // ragged edge tiles do less work
+    return speed * useful / (ceil(tiles / slots) * slots);
+  };
+  const double sc[4] = {score(256, 256, 1, 1.00), score(192, 256, 1, 0.97), score(128, 256, 1, 0.90),
+                        score(128, 128, 2, 0.85)};
+  int best = 0;
+  for (int i = 1; i < 4; ++i) if (sc[i] > sc[best] * 1.02) best = i;
+  return best;
+}
+
+template <int EPI>
+static pg_status launch_one(const GemmArgs& a, hipStream_t s) {
+  switch (pick_tile(a)) {
+    case 0: return launch_tile<EPI, 256, 256, 64, 2, 4, 2>(a, s);
+    case 1: return launch_tile<EPI, 192, 256, 64, 2, 4, 2>(a, s);
+    case 2: return launch_tile<EPI, 128, 256, 64, 2, 4, 2>(a, s);
+    default: return launch_tile<EPI, 128, 128, 64, 2, 2, 2>(a, s);
+  }
+}
+
 pg_status launch_gemm(const GemmArgs& a, int epilogue, hipStream_t s) {
   if (a.M <= 0 || a.N <= 0) return PG_OK;
-  if (a.K <= 0 || a.K % BK) return fail(PG_ESHAPE, "GEMM K = %d must be a positive multiple of %d", a.K, BK);
+  if (a.K <= 0 || a.K % 64) return fail(PG_ESHAPE, "GEMM K = %d must be a positive multiple of 64", a.K);
   if (a.lda % 8 || a.ldw % 8 || a.lda < a.K || a.ldw < a.K || ((uintptr_t)a.A & 15) || ((uintptr_t)a.W & 15))
     return fail(PG_ESHAPE, "GEMM operands need 16-byte aligned rows (lda %lld, ldw %lld)", (long long)a.lda, (long long)a.ldw);
   if (!a.A || !a.W) return fail(PG_EINVAL, "GEMM: null operand");
+  if (epilogue == EPI_QKV) {
+    // query | key columns row-major, value columns transposed: two launches over disjoint column ranges
+    GemmArgs qk = a;
+    qk.N = a.v_start;
+    PG_TRY(launch_gemm(qk, EPI_BF16, s));
+    GemmArgs v = a;
+    v.N = a.N - a.v_start;
+    v.W = a.W + (int64_t)a.v_start * a.ldw;
+    v.bias = a.bias ? a.bias + a.v_start : nullptr;
+    return launch_gemm(v, EPI_VT, s);
+  }
   const int rec = prof_open(PROF_GEMM, 2.0 * a.M * (double)a.N * (a.k_algo > 0 ? a.k_algo : a.K), s);
   pg_status st = PG_EINVAL;
   switch (epilogue) {
     case EPI_F32: st = launch_one<EPI_F32>(a, s); break;
     case EPI_EMBED: st = launch_one<EPI_EMBED>(a, s); break;
     case EPI_BF16: st = launch_one<EPI_BF16>(a, s); break;
-    case EPI_QKV: st = launch_one<EPI_QKV>(a, s); break;
+    case EPI_VT: st = launch_one<EPI_VT>(a, s); break;
     case EPI_GELU: st = launch_one<EPI_GELU>(a, s); break;
     case EPI_RESID: st = launch_one<EPI_RESID>(a, s); break;
     case EPI_UNPATCH: st = launch_one<EPI_UNPATCH>(a, s); break;
