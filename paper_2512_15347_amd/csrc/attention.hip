@@ -16,6 +16,8 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
+typedef float f32x2v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int ATT_THREADS = 256;
 constexpr int QTILE = 128, KTILE = 64;
@@ -30,7 +32,7 @@ __device__ __forceinline__ int v_off(int row, int chunk) {       // V^T tile [HD
 }
 
 template <int HD>
-__global__ __launch_bounds__(ATT_THREADS) void attention_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(const AttnArgs a) {
   constexpr int KCH = HD / 8;                  // 16-byte chunks per K row
   constexpr int K_PER_THREAD = KTILE * KCH / ATT_THREADS;        // 2 (HD 64) or 1 (HD 32)
   constexpr int V_PER_THREAD = HD * 8 / ATT_THREADS;             // 2 or 1
@@ -61,26 +63,33 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(const AttnArgs a
   for (int t = 0; t < OT; ++t)
 #pragma unroll
     for (int e = 0; e < 16; ++e) o[t][e] = 0.f;
+  // Running softmax statistics in the log2 domain.  m_run is a reference exponent, not necessarily the
+  // exact running maximum: it is only raised (and the accumulators rescaled) when a new score exceeds
+  // it by more than 2^8, so most tiles skip the rescale; probabilities stay below 2^8, well inside
+  // bf16 / fp32 range, and the final division by l makes the result independent of the reference.
   float m_run = -__builtin_huge_valf(), l_run = 0.f;
+  const float c = a.scale_log2;
 
   const int n_tiles = (a.Lk + KTILE - 1) / KTILE;
   u32x4v rk[K_PER_THREAD], rv[V_PER_THREAD];
+  // per-lane staging positions (fixed), advanced by whole tiles
+  int k_row[K_PER_THREAD], k_ch[K_PER_THREAD], v_row[V_PER_THREAD], v_ch[V_PER_THREAD];
+#pragma unroll
+  for (int i = 0; i < K_PER_THREAD; ++i) { const int cc = tid + i * ATT_THREADS; k_row[i] = cc / KCH; k_ch[i] = cc % KCH; }
+#pragma unroll
+  for (int i = 0; i < V_PER_THREAD; ++i) { const int cc = tid + i * ATT_THREADS; v_row[i] = cc >> 3; v_ch[i] = cc & 7; }
 
   auto load_tile = [&](int kt) {
     const int k0 = kt * KTILE;
 #pragma unroll
     for (int i = 0; i < K_PER_THREAD; ++i) {
-      const int c = tid + i * ATT_THREADS;
-      const int row = c / KCH, ch = c % KCH;
-      const int key = min(k0 + row, a.Lk - 1);
-      rk[i] = *reinterpret_cast<const u32x4v*>(kbase + (int64_t)key * a.ldk + ch * 8);
+      const int key = min(k0 + k_row[i], a.Lk - 1);
+      rk[i] = *reinterpret_cast<const u32x4v*>(kbase + (int64_t)key * a.ldk + k_ch[i] * 8);
     }
 #pragma unroll
     for (int i = 0; i < V_PER_THREAD; ++i) {
-      const int c = tid + i * ATT_THREADS;
-      const int row = c >> 3, ch = c & 7;
-      const int kc = k0 + ch * 8;
-      u32x4v v = *reinterpret_cast<const u32x4v*>(vbase + (int64_t)row * a.Lkpad + kc);
+      const int kc = k0 + v_ch[i] * 8;
+      u32x4v v = *reinterpret_cast<const u32x4v*>(vbase + (int64_t)v_row[i] * a.Lkpad + kc);
       if (kc + 8 > a.Lk) {                       // zero the keys past the end (padding may hold anything)
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
@@ -95,15 +104,9 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(const AttnArgs a
   };
   auto store_tile = [&]() {
 #pragma unroll
-    for (int i = 0; i < K_PER_THREAD; ++i) {
-      const int c = tid + i * ATT_THREADS;
-      *reinterpret_cast<u32x4v*>(sK + k_off<HD>(c / KCH, c % KCH)) = rk[i];
-    }
+    for (int i = 0; i < K_PER_THREAD; ++i) *reinterpret_cast<u32x4v*>(sK + k_off<HD>(k_row[i], k_ch[i])) = rk[i];
 #pragma unroll
-    for (int i = 0; i < V_PER_THREAD; ++i) {
-      const int c = tid + i * ATT_THREADS;
-      *reinterpret_cast<u32x4v*>(sV + v_off(c >> 3, c & 7)) = rv[i];
-    }
+    for (int i = 0; i < V_PER_THREAD; ++i) *reinterpret_cast<u32x4v*>(sV + v_off(v_row[i], v_ch[i])) = rv[i];
   };
 
   load_tile(0);
@@ -127,36 +130,45 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(const AttnArgs a
     }
     // ---- online softmax for this lane's query ----
     const int k0 = kt * KTILE;
-    float mx = -__builtin_huge_valf();
+    if (k0 + KTILE > a.Lk) {                     // only the last tile can hold keys past the end
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (k0 + t * 32 + 8 * (e >> 2) + 4 * half + (e & 3) >= a.Lk) s[t][e] = -__builtin_huge_valf();
+    }
+    float mx = s[0][0];
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int key = k0 + t * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-        float v = s[t][e] * a.scale_log2;
-        if (key >= a.Lk) v = -__builtin_huge_valf();
-        s[t][e] = v;
-        mx = fmaxf(mx, v);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    m_run = m_new;
+      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[t][e]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE)) * c;
+    if (__builtin_amdgcn_ballot_w64(mx > m_run + 8.0f) != 0ull) {     // wave-uniform: rare after the first tile
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int t = 0; t < OT; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
+    }
+    const float neg_m = -m_run;
     float psum = 0.f;
     bf16x8 pf[2][2];
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const float p = __builtin_amdgcn_exp2f(s[t][e] - m_new);
-        psum += p;
-        pf[t][e >> 3][e & 7] = (__bf16)p;
+      for (int e = 0; e < 16; e += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[t][e], c, neg_m));
+        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[t][e + 1], c, neg_m));
+        psum += p0 + p1;
+        const f32x2v pp = {p0, p1};
+        const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+        pf[t][e >> 3][e & 7] = pb[0];
+        pf[t][e >> 3][(e & 7) + 1] = pb[1];
       }
-    l_run = l_run * alpha + psum;
-#pragma unroll
-    for (int t = 0; t < OT; ++t)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
+    l_run += psum;
     // ---- O^T += V^T P^T : contraction over 16 keys per MFMA, keys permuted as the accumulator holds them ----
 #pragma unroll
     for (int t = 0; t < 2; ++t)
