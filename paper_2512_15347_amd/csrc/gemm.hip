@@ -24,9 +24,24 @@ constexpr int XCDS = 8;
 
 // byte offset of 16-byte chunk `chunk` of tile row `row` inside an operand tile with CH chunks per row
 template <int CH>
-__device__ __forceinline__ int lds_off(int row, int chunk) {
-  if (CH == 8) return (row * 8 + (chunk ^ ((row ^ (row >> 3)) & 7))) * 16;
-  return (row * 4 + (chunk ^ (((row >> 1) ^ (row >> 3)) & 3))) * 16;
+__device__ __forceinline__ int swz(int row) {
+  return CH == 8 ? ((row ^ (row >> 3)) & 7) : (((row >> 1) ^ (row >> 3)) & 3);
+}
+template <int CH>
+__device__ __forceinline__ int lds_off(int row, int chunk) { return (row * CH + (chunk ^ swz<CH>(row))) * 16; }
+
+// 16 bytes per lane straight from global memory into LDS (no register staging): the wave writes the
+// 1 KB starting at LDS address `lds_addr` (wave-uniform), lane l at +16 l.  Issued through inline
+// assembly so that the operand reads of the other LDS stage are not made to wait for it; completion
+// is awaited explicitly (wait_dma) before the barrier that publishes the stage.
+__device__ __forceinline__ void dma16(const uint16_t* g, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory");
+}
+// wait until at most N of this wave's loads are still in flight (loads complete in order)
+template <int N>
+__device__ __forceinline__ void wait_dma() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
 __device__ __forceinline__ float gelu_tanh(float x) {
@@ -40,25 +55,25 @@ __device__ __forceinline__ float gelu_tanh(float x) {
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __builtin_bit_cast(float, (uint32_t)b << 16); }
 __device__ __forceinline__ uint16_t f32_to_bf16(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
 
-template <int EPI, int BM, int BN, int BK, int WM, int WN, int MINW>
+template <int EPI, int BM, int BN, int BK, int WM, int WN, int MINW, int NST>
 __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs a) {
+  constexpr bool DMA = NST > 0;                    // NST LDS stages filled by direct loads; 0: register staging
   constexpr int THREADS = 64 * WM * WN;
   constexpr int CH = BK / 8;                       // 16-byte chunks per tile row
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;   // 32x32 MFMA tiles per wave
   constexpr int A_BYTES = BM * BK * 2, W_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + W_BYTES;
   constexpr int A_LD = BM * CH / THREADS, W_LD = BN * CH / THREADS;   // chunks staged per lane
   constexpr bool TR = (EPI == EPI_VT);             // accumulate the transposed 32x32 tiles
-  static_assert(BM * CH % THREADS == 0 && BN * CH % THREADS == 0, "staging must divide evenly");
   extern __shared__ __align__(16) unsigned char smem[];
   // ---- which output tile: XCD-aware, banded raster ----
   const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
   const int total = tiles_m * tiles_n;
   const int per_xcd = gridDim.x / XCDS;
-  const int b = (blockIdx.x % XCDS) * per_xcd + blockIdx.x / XCDS;
+  const int b = a.raster ? (blockIdx.x % XCDS) * per_xcd + blockIdx.x / XCDS : blockIdx.x;
   if (b >= total) return;
-  const int band = GROUP_M * tiles_n;
-  const int first_m = (b / band) * GROUP_M;
-  const int gsz = min(tiles_m - first_m, GROUP_M);
+  const int band = a.group_m * tiles_n;
+  const int first_m = (b / band) * a.group_m;
+  const int gsz = min(tiles_m - first_m, a.group_m);
   const int tm = first_m + (b % band) % gsz;
   const int tn = (b % band) / gsz;
   const int m0 = tm * BM, n0 = tn * BN;
@@ -67,22 +82,6 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
   const int wm = wave / WN, wn = wave % WN;
   const int l32 = lane & 31, half = lane >> 5;
 
-  // ---- staging assignment ----
-  const uint16_t* a_ptr[A_LD];
-  const uint16_t* w_ptr[W_LD];
-  int a_st[A_LD], w_st[W_LD];
-#pragma unroll
-  for (int i = 0; i < A_LD; ++i) {
-    const int c = tid + i * THREADS, row = c / CH, ch = c % CH;
-    a_ptr[i] = a.A + (int64_t)min(m0 + row, a.M - 1) * a.lda + ch * 8;
-    a_st[i] = lds_off<CH>(row, ch);
-  }
-#pragma unroll
-  for (int i = 0; i < W_LD; ++i) {
-    const int c = tid + i * THREADS, row = c / CH, ch = c % CH;
-    w_ptr[i] = a.W + (int64_t)min(n0 + row, a.N - 1) * a.ldw + ch * 8;
-    w_st[i] = A_BYTES + lds_off<CH>(row, ch);
-  }
   int a_row[TM], w_row[TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i) a_row[i] = wm * (BM / WM) + i * 32 + l32;
@@ -97,32 +96,11 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  u32x4v ra[A_LD], rw[W_LD];
   const int nk = a.K / BK;
-  auto load_regs = [&](int kt) {
-#pragma unroll
-    for (int i = 0; i < A_LD; ++i) ra[i] = *reinterpret_cast<const u32x4v*>(a_ptr[i] + kt * BK);
-#pragma unroll
-    for (int i = 0; i < W_LD; ++i) rw[i] = *reinterpret_cast<const u32x4v*>(w_ptr[i] + kt * BK);
-  };
-  auto store_regs = [&](int stage) {
-    unsigned char* d = smem + stage * STAGE_BYTES;
-#pragma unroll
-    for (int i = 0; i < A_LD; ++i) *reinterpret_cast<u32x4v*>(d + a_st[i]) = ra[i];
-#pragma unroll
-    for (int i = 0; i < W_LD; ++i) *reinterpret_cast<u32x4v*>(d + w_st[i]) = rw[i];
-  };
-  load_regs(0);
-  store_regs(0);
-  if (nk > 1) load_regs(1);
-  __syncthreads();
-
-  for (int kt = 0; kt < nk; ++kt) {
-    // registers hold tile kt+1: park it in the other stage (last read before the previous barrier),
-    // then start fetching tile kt+2 so that a whole iteration hides its latency
-    if (kt + 1 < nk) store_regs((kt + 1) & 1);
-    if (kt + 2 < nk) load_regs(kt + 2);
-    const unsigned char* sA = smem + (kt & 1) * STAGE_BYTES;
+  // One K step of MFMAs from LDS stage `stage`; `between(ks)` runs after the operand reads of slab ks
+  // have been issued and before its MFMAs (the direct-load path spreads its requests there).
+  auto multiply_stage = [&](int stage, auto&& between) {
+    const unsigned char* sA = smem + stage * STAGE_BYTES;
     const unsigned char* sW = sA + A_BYTES;
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
@@ -131,6 +109,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
       for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const bf16x8*>(sA + lds_off<CH>(a_row[i], 2 * ks + half));
 #pragma unroll
       for (int j = 0; j < TN; ++j) wf[j] = *reinterpret_cast<const bf16x8*>(sW + lds_off<CH>(w_row[j], 2 * ks + half));
+      between(ks);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -138,7 +117,107 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
           acc[i][j] = TR ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], af[i], acc[i][j], 0, 0, 0)
                          : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], wf[j], acc[i][j], 0, 0, 0);
     }
+  };
+
+  if constexpr (DMA) {
+    // ---- global -> LDS directly: every wave owns N_REG / WAVES regions of 1 KB (64 / CH tile rows) ----
+    constexpr int WAVES = WM * WN, RPR = 64 / CH;
+    constexpr int A_REG = BM / RPR, N_REG = (BM + BN) / RPR, PER_WAVE = N_REG / WAVES;
+    static_assert(N_REG % WAVES == 0, "regions must divide among the waves");
+    const uint16_t* g_ptr[PER_WAVE];
+    uint32_t g_lds[PER_WAVE];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)smem;
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; ++i) {
+      const int g = wave + i * WAVES;                 // wave-uniform region id
+      const bool is_w = g >= A_REG;
+      const int rg = is_w ? g - A_REG : g;
+      const int row = rg * RPR + lane / CH;
+      const int ch = (lane % CH) ^ swz<CH>(row);
+      g_ptr[i] = is_w ? a.W + (int64_t)min(n0 + row, a.N - 1) * a.ldw + ch * 8
+                      : a.A + (int64_t)min(m0 + row, a.M - 1) * a.lda + ch * 8;
+      g_lds[i] = __builtin_amdgcn_readfirstlane(lds_base + (is_w ? A_BYTES : 0) + rg * 1024);
+    }
+    auto issue = [&](int kt, int stage) {
+#pragma unroll
+      for (int i = 0; i < PER_WAVE; ++i) dma16(g_ptr[i] + kt * BK, g_lds[i] + stage * STAGE_BYTES);
+    };
+    // NST stages in flight: tile kt+NST-1 is requested while tile kt is multiplied.  At the barrier of
+    // iteration kt every wave has its share of tile kt in LDS (all but the loads of the NST-2 younger
+    // tiles have landed) and has finished reading stage (kt-1) % NST, which is the one refilled next.
+    // The requests of one wave are spread over half of the K step's MFMA slabs, and the two waves that
+    // share a SIMD (wave, wave + 4) use opposite halves: a wave waiting for the texture-address unit to
+    // take its request cannot issue MFMAs, its partner can.
+    constexpr int SLABS = BK / 16, HALF = SLABS / 2 > 0 ? SLABS / 2 : 1;
+    constexpr int PER_SLAB = (PER_WAVE + HALF - 1) / HALF;
+    const int my_half = __builtin_amdgcn_readfirstlane((SLABS >= 2) ? ((wave >> 2) & 1) * HALF : 0);
+#pragma unroll
+    for (int t = 0; t < NST - 1; ++t)
+      if (t < nk) issue(t, t);
+    for (int kt = 0; kt < nk; ++kt) {
+      if (kt + NST - 1 <= nk) wait_dma<PER_WAVE * (NST - 2)>();
+      else wait_dma<0>();                          // tail: fewer tiles are in flight than the steady state
+      __syncthreads();
+      const int kn = kt + NST - 1;
+      const bool more = kn < nk;
+      const int nstage = kn % NST;
+      multiply_stage(kt % NST, [&](int ks) {
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int sl = 0; sl < HALF; ++sl)
+          if (more && ks - my_half == sl) {
+#pragma unroll
+            for (int i = 0; i < PER_SLAB; ++i)
+              if (sl * PER_SLAB + i < PER_WAVE)
+                dma16(g_ptr[sl * PER_SLAB + i] + kn * BK, g_lds[sl * PER_SLAB + i] + nstage * STAGE_BYTES);
+          }
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    }
+  } else {
+    // ---- global -> registers -> LDS ----
+    static_assert(BM * CH % THREADS == 0 && BN * CH % THREADS == 0, "staging must divide evenly");
+    const uint16_t* a_ptr[A_LD];
+    const uint16_t* w_ptr[W_LD];
+    int a_st[A_LD], w_st[W_LD];
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) {
+      const int c = tid + i * THREADS, row = c / CH, ch = c % CH;
+      a_ptr[i] = a.A + (int64_t)min(m0 + row, a.M - 1) * a.lda + ch * 8;
+      a_st[i] = lds_off<CH>(row, ch);
+    }
+#pragma unroll
+    for (int i = 0; i < W_LD; ++i) {
+      const int c = tid + i * THREADS, row = c / CH, ch = c % CH;
+      w_ptr[i] = a.W + (int64_t)min(n0 + row, a.N - 1) * a.ldw + ch * 8;
+      w_st[i] = A_BYTES + lds_off<CH>(row, ch);
+    }
+    u32x4v ra[A_LD], rw[W_LD];
+    auto load_regs = [&](int kt) {
+#pragma unroll
+      for (int i = 0; i < A_LD; ++i) ra[i] = *reinterpret_cast<const u32x4v*>(a_ptr[i] + kt * BK);
+#pragma unroll
+      for (int i = 0; i < W_LD; ++i) rw[i] = *reinterpret_cast<const u32x4v*>(w_ptr[i] + kt * BK);
+    };
+    auto store_regs = [&](int stage) {
+      unsigned char* d = smem + stage * STAGE_BYTES;
+#pragma unroll
+      for (int i = 0; i < A_LD; ++i) *reinterpret_cast<u32x4v*>(d + a_st[i]) = ra[i];
+#pragma unroll
+      for (int i = 0; i < W_LD; ++i) *reinterpret_cast<u32x4v*>(d + w_st[i]) = rw[i];
+    };
+    load_regs(0);
+    store_regs(0);
+    if (nk > 1) load_regs(1);
     __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+      // registers hold tile kt+1: park it in the other stage (last read before the previous barrier),
+      // then start fetching tile kt+2 so that a whole iteration hides its latency
+      if (kt + 1 < nk) store_regs((kt + 1) & 1);
+      if (kt + 2 < nk) load_regs(kt + 2);
+      multiply_stage(kt & 1, [](int) {});
+      __syncthreads();
+    }
   }
 
   // ---- epilogue: in each 32x32 tile a lane holds ONE column (l32) and rows 8q + 4*half + t ----
@@ -246,18 +325,18 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
   }
 }
 
-template <int EPI, int BM, int BN, int BK, int WM, int WN, int MINW>
+template <int EPI, int BM, int BN, int BK, int WM, int WN, int MINW, int NST>
 static pg_status launch_tile(const GemmArgs& a, hipStream_t s) {
-  constexpr int LDS = 2 * (BM + BN) * BK * 2;
+  constexpr int LDS = (NST > 0 ? NST : 2) * (BM + BN) * BK * 2;
   static bool attr_set = false;
   if (!attr_set) {
-    PG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel<EPI, BM, BN, BK, WM, WN, MINW>),
+    PG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel<EPI, BM, BN, BK, WM, WN, MINW, NST>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS));
     attr_set = true;
   }
   const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
   const int grid = (tiles + XCDS - 1) / XCDS * XCDS;
-  gemm_kernel<EPI, BM, BN, BK, WM, WN, MINW><<<dim3(grid), dim3(64 * WM * WN), LDS, s>>>(a);
+  gemm_kernel<EPI, BM, BN, BK, WM, WN, MINW, NST><<<dim3(grid), dim3(64 * WM * WN), LDS, s>>>(a);
   PG_LAUNCH_CHECK("gemm_kernel");
   return PG_OK;
 }
@@ -284,15 +363,28 @@ static int pick_tile(const GemmArgs& a) {
 
 template <int EPI>
 static pg_status launch_one(const GemmArgs& a, hipStream_t s) {
-  switch (pick_tile(a)) {
-    case 0: return launch_tile<EPI, 256, 256, 64, 2, 4, 2>(a, s);
-    case 1: return launch_tile<EPI, 192, 256, 64, 2, 4, 2>(a, s);
-    case 2: return launch_tile<EPI, 128, 256, 64, 2, 4, 2>(a, s);
-    default: return launch_tile<EPI, 128, 128, 64, 2, 2, 2>(a, s);
+  static const bool dma = [] { const char* e = getenv("PROGRPO_GEMM_STAGING"); return !(e && e[0] == 'r'); }();
+  if (dma) {
+    switch (pick_tile(a)) {
+      case 0: return launch_tile<EPI, 256, 256, 64, 2, 4, 2, 2>(a, s);
+      case 1: return launch_tile<EPI, 192, 256, 64, 2, 4, 2, 2>(a, s);
+      case 2: return launch_tile<EPI, 128, 256, 64, 2, 4, 2, 2>(a, s);
+      default: return launch_tile<EPI, 128, 128, 64, 2, 2, 2, 2>(a, s);
+    }
+  }
+  switch (pick_tile(a)) {      // PROGRPO_GEMM_STAGING=regs: staging through registers (tuning aid)
+    case 0: return launch_tile<EPI, 256, 256, 64, 2, 4, 2, 0>(a, s);
+    case 1: return launch_tile<EPI, 192, 256, 64, 2, 4, 2, 0>(a, s);
+    case 2: return launch_tile<EPI, 128, 256, 64, 2, 4, 2, 0>(a, s);
+    default: return launch_tile<EPI, 128, 128, 64, 2, 2, 2, 0>(a, s);
   }
 }
 
-pg_status launch_gemm(const GemmArgs& a, int epilogue, hipStream_t s) {
+pg_status launch_gemm(const GemmArgs& a_in, int epilogue, hipStream_t s) {
+  GemmArgs a = a_in;
+  static const int raster = [] { const char* e = getenv("PROGRPO_GEMM_RASTER"); return e ? atoi(e) : 1; }();
+  static const int group_m = [] { const char* e = getenv("PROGRPO_GEMM_GROUP_M"); return e ? atoi(e) : GROUP_M; }();
+  a.raster = raster; a.group_m = group_m;
   if (a.M <= 0 || a.N <= 0) return PG_OK;
   if (a.K <= 0 || a.K % 64) return fail(PG_ESHAPE, "GEMM K = %d must be a positive multiple of 64", a.K);
   if (a.lda % 8 || a.ldw % 8 || a.lda < a.K || a.ldw < a.K || ((uintptr_t)a.A & 15) || ((uintptr_t)a.W & 15))

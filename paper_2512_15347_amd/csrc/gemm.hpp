@@ -29,6 +29,7 @@ struct GemmArgs {
   uint16_t* vt; int v_start, Lpad;
   const float* gate; int64_t gate_ld; const int32_t* group_of;
   int Wp, HW, Wimg;                // unpatchify: patches per row, H*W, W
+  int raster, group_m;             // tile order: XCD-aware remap on/off, tile rows per band (set by the launcher)
 };
 
 pg_status launch_gemm(const GemmArgs& a, int epilogue, hipStream_t s);
