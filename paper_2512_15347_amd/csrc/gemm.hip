@@ -44,12 +44,21 @@ __device__ __forceinline__ void wait_dma() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+// gelu_tanh(x) = x/2 (1 + tanh(y)) = x / (1 + exp(-2y)),  y = sqrt(2/pi) (x + 0.044715 x^3);
+// the exponent is taken in base 2: -2 y log2(e) = x (K1 + K3 x^2)
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
 __device__ __forceinline__ float gelu_tanh(float x) {
-  const float y = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-  // tanh(y) = 1 - 2 / (exp(2y) + 1)
-  const float e = __builtin_amdgcn_exp2f(2.8853900817779268f * y);
-  const float t = 1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f);
-  return 0.5f * x * (1.0f + t);
+  constexpr float K1 = -2.0f * 0.7978845608028654f * 1.4426950408889634f;
+  constexpr float K3 = K1 * 0.044715f;
+  const float z = x * __builtin_fmaf(x * x, K3, K1);
+  return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(z));
+}
+
+__device__ __forceinline__ uint2 pack_bf16x4(float4 v) {
+  uint2 r;
+  r.x = (uint32_t)f32_to_bf16_bits(v.x) | ((uint32_t)f32_to_bf16_bits(v.y) << 16);
+  r.y = (uint32_t)f32_to_bf16_bits(v.z) | ((uint32_t)f32_to_bf16_bits(v.w) << 16);
+  return r;
 }
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __builtin_bit_cast(float, (uint32_t)b << 16); }
@@ -245,6 +254,94 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
     }
     return;
   }
+  if constexpr (EPI != EPI_UNPATCH) {
+    // ---- row-major epilogues: transpose each 32-row slab of the wave tile through LDS so that a lane
+    // owns 4 consecutive columns of a row and every global access is 16 bytes wide (8 for bf16) ----
+    static_assert(TN == 2, "the staged epilogue assumes 64 columns per wave");
+    constexpr int EST = TN * 32 + 8;                 // staging row stride in floats (half-waves hit disjoint banks)
+    __syncthreads();                                 // every wave has finished reading the last stage
+    float* stg = reinterpret_cast<float*>(smem) + wave * (32 * EST);
+    const int c4 = (lane & 15) * 4, rsub = lane >> 4;
+    const int n = n0 + wn * (BN / WN) + c4;
+    const bool n_ok = n < a.N;                       // N is a multiple of 4
+    float4 b4 = {0.f, 0.f, 0.f, 0.f};
+    if (a.bias && n_ok) {
+      const uint2 raw = *reinterpret_cast<const uint2*>(a.bias + n);
+      b4 = {bf16_to_f32((uint16_t)raw.x), bf16_to_f32((uint16_t)(raw.x >> 16)), bf16_to_f32((uint16_t)raw.y),
+            bf16_to_f32((uint16_t)(raw.y >> 16))};
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int slab0 = m0 + wm * (BM / WM) + i * 32;            // wave-uniform
+      if (slab0 >= a.M) break;
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int t = 0; t < 4; ++t) stg[(8 * q + 4 * half + t) * EST + j * 32 + l32] = acc[i][j][4 * q + t];
+      float4 v[8];
+#pragma unroll
+      for (int p = 0; p < 8; ++p) {
+        v[p] = *reinterpret_cast<const float4*>(stg + (4 * p + rsub) * EST + c4);
+        v[p].x += b4.x; v[p].y += b4.y; v[p].z += b4.z; v[p].w += b4.w;
+      }
+      if (EPI == EPI_RESID) {
+        // gates are per (group, column); a slab of 32 rows touches at most two trajectories when a
+        // trajectory has at least 32 rows.  All loads of the slab are issued before its stores.
+        float4 g0 = {1.f, 1.f, 1.f, 1.f}, g1 = g0;
+        const bool fast = a.L >= 32;
+        const int traj0 = slab0 / a.L;
+        const int split = (traj0 + 1) * a.L;
+        if (a.gate && fast && n_ok) {
+          const int last = (a.M - 1) / a.L;
+          g0 = *reinterpret_cast<const float4*>(a.gate + (int64_t)a.group_of[traj0] * a.gate_ld + n);
+          g1 = *reinterpret_cast<const float4*>(a.gate + (int64_t)a.group_of[min(traj0 + 1, last)] * a.gate_ld + n);
+        }
+        float4 hv[8], gv[8];
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+          const int r = slab0 + 4 * p + rsub;
+          const bool ok = r < a.M && n_ok;
+          hv[p] = ok ? *reinterpret_cast<const float4*>(a.outf + (int64_t)r * a.ldo + n) : float4{0.f, 0.f, 0.f, 0.f};
+          gv[p] = r < split ? g0 : g1;
+          if (a.gate && !fast && ok)
+            gv[p] = *reinterpret_cast<const float4*>(a.gate + (int64_t)a.group_of[r / a.L] * a.gate_ld + n);
+        }
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+          const int r = slab0 + 4 * p + rsub;
+          if (r < a.M && n_ok) {
+            float4 o = {hv[p].x + gv[p].x * v[p].x, hv[p].y + gv[p].y * v[p].y, hv[p].z + gv[p].z * v[p].z,
+                        hv[p].w + gv[p].w * v[p].w};
+            *reinterpret_cast<float4*>(a.outf + (int64_t)r * a.ldo + n) = o;
+          }
+        }
+        continue;
+      }
+#pragma unroll
+      for (int p = 0; p < 8; ++p) {
+        const int r = slab0 + 4 * p + rsub;
+        if (r >= a.M || !n_ok) continue;
+        if (EPI == EPI_F32) {
+          *reinterpret_cast<float4*>(a.outf + (int64_t)r * a.ldo + n) = v[p];
+        } else if (EPI == EPI_EMBED) {
+          const int traj = r / a.Li, tok = r - traj * a.Li;
+          const uint2 raw = *reinterpret_cast<const uint2*>(a.pos + (int64_t)tok * a.N + n);
+          float4 o = {v[p].x + bf16_to_f32((uint16_t)raw.x), v[p].y + bf16_to_f32((uint16_t)(raw.x >> 16)),
+                      v[p].z + bf16_to_f32((uint16_t)raw.y), v[p].w + bf16_to_f32((uint16_t)(raw.y >> 16))};
+          *reinterpret_cast<float4*>(a.outf + ((int64_t)traj * a.L + tok) * a.ldo + n) = o;
+        } else if (EPI == EPI_BF16) {
+          *reinterpret_cast<uint2*>(a.outb + (int64_t)r * a.ldob + n) = pack_bf16x4(v[p]);
+        } else if (EPI == EPI_GELU) {
+          const float4 gl = {gelu_tanh(v[p].x), gelu_tanh(v[p].y), gelu_tanh(v[p].z), gelu_tanh(v[p].w)};
+          *reinterpret_cast<uint2*>(a.outb + (int64_t)r * a.ldob + n) = pack_bf16x4(gl);
+        }
+      }
+    }
+    return;
+  }
+  // ---- unpatchify: per-element scatter into the latent layout (small: N = 4C columns) ----
   int n_j[TN];
   float bias_j[TN];
 #pragma unroll
@@ -255,43 +352,11 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int rb = m0 + wm * (BM / WM) + i * 32 + 4 * half;       // rows rb + 8q + t
-    if (EPI == EPI_RESID) {
-      // phase 1: every load of this 32-row slab (old h, gates) is issued before the first store,
-      // so the memory latencies overlap instead of chaining through possible aliasing
-      float hv[4][TN][4], gv[4][TN][4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const int r = rb + 8 * q + t;
-          const bool ok = r < a.M;
-          int gid = 0;
-          if (a.gate && ok) gid = a.group_of[r / a.L];
-#pragma unroll
-          for (int j = 0; j < TN; ++j) {
-            const bool okn = ok && n_j[j] < a.N;
-            hv[q][j][t] = okn ? a.outf[(int64_t)r * a.ldo + n_j[j]] : 0.f;
-            gv[q][j][t] = (a.gate && okn) ? a.gate[(int64_t)gid * a.gate_ld + n_j[j]] : 1.0f;
-          }
-        }
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const int r = rb + 8 * q + t;
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            if (r < a.M && n_j[j] < a.N)
-              a.outf[(int64_t)r * a.ldo + n_j[j]] = hv[q][j][t] + gv[q][j][t] * (acc[i][j][4 * q + t] + bias_j[j]);
-        }
-      continue;
-    }
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int r0 = rb + 8 * q;
       if (r0 >= a.M) continue;
-      int traj0 = 0, tok0 = 0;
-      if (EPI == EPI_EMBED || EPI == EPI_UNPATCH) { traj0 = r0 / a.Li; tok0 = r0 - traj0 * a.Li; }
+      const int traj0 = r0 / a.Li, tok0 = r0 - traj0 * a.Li;
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int n = n_j[j];
@@ -302,23 +367,11 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
           const int r = r0 + t;
           if (r >= a.M) break;
           const float v = acc[i][j][4 * q + t] + bias_j[j];
-          if (EPI == EPI_F32) {
-            a.outf[(int64_t)r * a.ldo + n] = v;
-          } else if (EPI == EPI_EMBED) {
-            if (tok >= a.Li) { tok -= a.Li; ++traj; }
-            a.outf[((int64_t)traj * a.L + tok) * a.ldo + n] = v + bf16_to_f32(a.pos[(int64_t)tok * a.N + n]);
-            ++tok;
-          } else if (EPI == EPI_BF16) {
-            a.outb[(int64_t)r * a.ldob + n] = f32_to_bf16(v);
-          } else if (EPI == EPI_GELU) {
-            a.outb[(int64_t)r * a.ldob + n] = f32_to_bf16(gelu_tanh(v));
-          } else if (EPI == EPI_UNPATCH) {
-            if (tok >= a.Li) { tok -= a.Li; ++traj; }
-            const int py = tok / a.Wp, px = tok - py * a.Wp;
-            const int c = n >> 2, dy = (n >> 1) & 1, dx = n & 1;
-            a.outf[(int64_t)traj * ((int64_t)(a.N >> 2) * a.HW) + (int64_t)c * a.HW + (2 * py + dy) * a.Wimg + 2 * px + dx] = v;
-            ++tok;
-          }
+          if (tok >= a.Li) { tok -= a.Li; ++traj; }
+          const int py = tok / a.Wp, px = tok - py * a.Wp;
+          const int c = n >> 2, dy = (n >> 1) & 1, dx = n & 1;
+          a.outf[(int64_t)traj * ((int64_t)(a.N >> 2) * a.HW) + (int64_t)c * a.HW + (2 * py + dy) * a.Wimg + 2 * px + dx] = v;
+          ++tok;
         }
       }
     }
@@ -390,6 +443,14 @@ pg_status launch_gemm(const GemmArgs& a_in, int epilogue, hipStream_t s) {
   if (a.lda % 8 || a.ldw % 8 || a.lda < a.K || a.ldw < a.K || ((uintptr_t)a.A & 15) || ((uintptr_t)a.W & 15))
     return fail(PG_ESHAPE, "GEMM operands need 16-byte aligned rows (lda %lld, ldw %lld)", (long long)a.lda, (long long)a.ldw);
   if (!a.A || !a.W) return fail(PG_EINVAL, "GEMM: null operand");
+  if (epilogue != EPI_UNPATCH && epilogue != EPI_VT && epilogue != EPI_QKV) {
+    // the row-major epilogues write 4 consecutive columns per lane
+    if (a.N % 4) return fail(PG_ESHAPE, "GEMM N = %d must be a multiple of 4", a.N);
+    if ((a.outf && (a.ldo % 4 || ((uintptr_t)a.outf & 15))) || (a.outb && (a.ldob % 4 || ((uintptr_t)a.outb & 7))) ||
+        (a.bias && ((uintptr_t)a.bias & 7)) || (a.gate && (a.gate_ld % 4 || ((uintptr_t)a.gate & 15))) ||
+        (a.pos && ((uintptr_t)a.pos & 7)))
+      return fail(PG_ESHAPE, "GEMM output / bias / gate rows need 16-byte (bf16: 8-byte) alignment");
+  }
   if (epilogue == EPI_QKV) {
     // query | key columns row-major, value columns transposed: two launches over disjoint column ranges
     GemmArgs qk = a;
