@@ -52,6 +52,61 @@ def cpu_baseline(cfg, w, inp, seed, budget_traj):
                 s_per_group=workloads_evals(cfg) / (n / dt) / cfg["P"])
 
 
+def stream_kernels_at_stress_shape(pg, torch, n=1024, d=16 * 128 * 128, reps=10):
+    """Fused update + log-prob, preview + reward and survivor compaction on 1024 x (16x128x128) fp32 latents:
+    algorithmic bytes / event-timed duration against the 8 TB/s HBM peak."""
+    dev = "cuda:0"
+    g = torch.Generator(device=dev); g.manual_seed(251215347)
+    x = torch.randn(n, d, device=dev, generator=g); u = torch.randn(n, d, device=dev, generator=g)
+    xo = torch.empty(n, d, device=dev)
+    w = torch.randn(d, device=dev, generator=g) / d ** 0.5
+    ids = torch.arange(n, dtype=torch.int32, device=dev)
+    r = torch.zeros(n, device=dev)
+    part = torch.zeros(pg.pg_step_scratch_floats(n, d), device=dev)
+    src = torch.arange(0, n, 2, dtype=torch.int32, device=dev)
+    res = {}
+
+    def timed(fn, nbytes):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        us = 1e3 * e0.elapsed_time(e1) / reps
+        gbs = nbytes / us / 1e3
+        return dict(us=round(us, 1), gbs=round(gbs, 1), frac_of_hbm_peak=round(gbs / PEAK_HBM_GBS, 4))
+
+    res["sde_step_logprob_1024x16x128x128"] = timed(
+        lambda: pg.pg_sde_step_logprob(x, u, xo, None, None, None, None, ids, n, d, 0.93, -0.1, 0.38, 7, 3, part), 12.0 * n * d)
+    res["preview_reward_1024x16x128x128"] = timed(
+        lambda: pg.pg_preview_reward(x, u, w, r, n, d, 1.0, -0.7, 0.1, part), 8.0 * n * d)
+    res["compact_gather_1024_to_512"] = timed(lambda: pg.pg_compact_gather(x, xo, src, n // 2, d), 8.0 * (n // 2) * d)
+    return res
+
+
+def recorded_gemm_traffic(workload):
+    """HBM bytes per GEMM launch from the committed counter summary, or None when there is none for this
+    workload or the kernel source has changed since the counters were taken."""
+    import hashlib
+    import re
+    path = os.path.join(ROOT, "profiles", f"gemm_kernel_{workload}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    text = open(path).read()
+    m_t = re.search(r"^traffic_bytes_per_launch=(\d+)", text, re.M)
+    m_h = re.search(r"^source_sha256=([0-9a-f]+)", text, re.M)
+    if not (m_t and m_h):
+        return None
+    h = hashlib.sha256()
+    for fn in ("gemm.hip", "gemm.hpp"):
+        h.update(open(os.path.join(ROOT, "paper_2512_15347_amd", "csrc", fn), "rb").read())
+    return int(m_t.group(1)) if h.hexdigest() == m_h.group(1) else None
+
+
 def workloads_evals(cfg):
     from paper_2512_15347_amd import workloads
     return workloads.network_evals(cfg)
@@ -107,7 +162,8 @@ def main():
     a = prof["attention"]
     s = prof["sde_step"]
     roofline = dict(bound="mfma", kernel="gemm_kernel (bf16 MFMA GEMM, all epilogues)", achieved=round(gemm_tflops, 2),
-                    peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=round(gemm_tflops / PEAK_BF16_TFLOPS, 4), traffic=None,
+                    peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
+                    traffic=recorded_gemm_traffic(args.workload),
                     launches=g["launches"], avg_launch_us=round(1e3 * g["ms"] / max(g["launches"], 1), 2),
                     share_of_step_time=round(g["ms"] * 1e-3 / dt, 4))
     others = dict(
@@ -116,6 +172,9 @@ def main():
         sde_step=dict(gbs=round(s["work"] / (s["ms"] * 1e-3) / 1e9, 1) if s["ms"] > 0 else None,
                       frac_of_hbm_peak=round(s["work"] / (s["ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) if s["ms"] > 0 else None,
                       share_of_step_time=round(s["ms"] * 1e-3 / dt, 4), launches=s["launches"]))
+
+    # the HBM-bound kernels at the stress shape (1024 trajectories of 16x128x128 fp32), outside the timed region
+    others.update(stream_kernels_at_stress_shape(pg, torch))
 
     out = dict(metric="trajectory-steps/s and s per group (N->k pruned sampling), 1 GPU",
                value=round(evals * args.steps / dt, 3), unit="trajectory-steps/s", n_gpus=1, steps=args.steps,
