@@ -234,7 +234,8 @@ pg_status pg_attention_bf16(const uint16_t *q, const uint16_t *k, const uint16_t
  * Between pg_profile_begin and pg_profile_end every launch of the heavy kernels is bracketed by a
  * pair of HIP events on the stream it is launched on (at most max_records launches are recorded).
  * pg_profile_read waits for the recorded events and returns, for one kind of kernel, the summed
- * durations [ms], the summed algorithmic work and the number of launches.
+ * durations [ms] (each less the duration an empty event pair reads on that stream, measured once at
+ * the first bracket), the summed algorithmic work and the number of launches.
  * kind 0: MFMA GEMM (work = 2 M N K flops), 1: attention (4 B heads Lq Lk hd flops),
  * 2: fused update + log-prob (12 bytes per latent element), 3: preview / reward (8 or 4 bytes per element). */
 pg_status pg_profile_begin(int32_t max_records);

@@ -22,9 +22,30 @@ struct ProfRec { int kind; double work; hipEvent_t a, b; bool closed; };
 static std::vector<ProfRec> g_prof;
 static bool g_prof_on = false;
 static size_t g_prof_cap = 0;
+static double g_prof_empty_ms = -1.0;    // duration an empty bracket reads (event processing), subtracted per record
+
+// Median of a few back-to-back event pairs with nothing between them on this stream.
+static void prof_calibrate(hipStream_t s) {
+  g_prof_empty_ms = 0.0;
+  float v[9];
+  int n = 0;
+  for (int i = 0; i < 9; ++i) {
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess) break;
+    if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); break; }
+    (void)hipEventRecord(a, s);
+    (void)hipEventRecord(b, s);
+    float t = 0.f;
+    if (hipEventSynchronize(b) == hipSuccess && hipEventElapsedTime(&t, a, b) == hipSuccess) v[n++] = t;
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+  }
+  if (n > 0) { std::sort(v, v + n); g_prof_empty_ms = v[n / 2]; }
+}
 
 int prof_open(int kind, double work, hipStream_t s) {
   if (!g_prof_on || g_prof.size() >= g_prof_cap) return -1;
+  if (g_prof_empty_ms < 0.0) prof_calibrate(s);
   ProfRec r{kind, work, nullptr, nullptr, false};
   if (hipEventCreate(&r.a) != hipSuccess) return -1;
   if (hipEventCreate(&r.b) != hipSuccess) { (void)hipEventDestroy(r.a); return -1; }
@@ -180,6 +201,7 @@ extern "C" pg_status pg_profile_begin(int32_t max_records) {
   g_prof.clear();
   g_prof.reserve(max_records);
   g_prof_cap = (size_t)max_records;
+  g_prof_empty_ms = -1.0;
   g_prof_on = true;
   return PG_OK;
 }
@@ -193,7 +215,7 @@ extern "C" pg_status pg_profile_read(int32_t kind, double* total_ms, double* tot
     PG_HIP(hipEventSynchronize(r.b));
     float t = 0.f;
     PG_HIP(hipEventElapsedTime(&t, r.a, r.b));
-    ms += t; work += r.work; ++n;
+    ms += std::max(0.0, (double)t - std::max(0.0, g_prof_empty_ms)); work += r.work; ++n;
   }
   if (total_ms) *total_ms = ms;
   if (total_work) *total_work = work;
