@@ -230,3 +230,55 @@ def test_forced_masks_follow_the_oracle(lib):
     lib.pg_check(ctx)
     _compare_final(lib, ctx, buf, cfg, rec, x_tol=2e-2)
     lib.pg_destroy(ctx)
+
+
+def test_paper_schedule_48_24_12_at_steps_5_7(lib):
+    """The paper's own flow schedule (Sec. 6.1: G_max = 48 pruned to 24 and 12 at steps 5 and 7 of T = 10)
+    on the small network: free-running library against the free-running oracle."""
+    name, seed = "paper_std_small", 2512
+    say(f"full loop {name}")
+    cfg, w, inp, tables, rec = _oracle(name, seed)
+    assert rec["active"] == [48] * 6 + [24] * 2 + [12] * 2
+    ctx, buf = _gpu_ctx(lib, cfg, w, inp)
+    lib.pg_sample_group(ctx, seed)
+    lib.pg_check(ctx)
+    _compare_final(lib, ctx, buf, cfg, rec, x_tol=2e-2)
+    lib.pg_destroy(ctx)
+
+
+def test_full_width_group_of_64_and_explicit_tables(lib):
+    """Largest group the selection takes (64, the paper's largest G_max), caller-supplied step tables,
+    a latent whose size is not a multiple of the streaming chunk."""
+    cfg = workloads.get_config("cfg1")
+    cfg.update(N=64, C=5, H=18, W=14, T=4, schedule=[[(1, 33), (2, 7)]])
+    cfg["d"] = 5 * 18 * 14
+    cfg["Li"] = 9 * 7
+    say("loop N=64 with explicit tables")
+    seed = 77
+    w = workloads.make_weights(cfg); inp = workloads.make_inputs(cfg, w)
+    tables = sampler.flow_sde_tables(4, 0.35)
+    rec = loop.run(cfg, tables, inp, seed, wts=w)
+    c, keep = lib.make_config(cfg, probe_bias=inp["probe_b"], tables=tables)
+    ctx = lib.pg_create(c)
+    buf = lib.Buffers(ctx, cfg, inputs=inp, weights_flat=lib.pack_weights(ctx, cfg, w))
+    lib.pg_bind(ctx, buf)
+    lib.pg_sample_group(ctx, seed)
+    lib.pg_check(ctx)
+    _compare_final(lib, ctx, buf, cfg, rec, x_tol=2e-2)
+    assert lib.pg_state(ctx, 1)["M"] == 7
+    lib.pg_destroy(ctx)
+
+
+def test_sample_group_is_repeatable_and_seed_dependent(lib):
+    cfg = workloads.get_config("cfg3_small")
+    w = workloads.make_weights(cfg); inp = workloads.make_inputs(cfg, w)
+    ctx, buf = _gpu_ctx(lib, cfg, w, inp)
+    outs = []
+    for seed in (5, 5, 6):
+        lib.pg_sample_group(ctx, seed)
+        lib.pg_check(ctx)
+        st = lib.pg_state(ctx, 1)
+        outs.append((buf.x[st["cur_x"]][:st["M"]].clone(), buf.logp_sum.clone(), buf.masks.clone()))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    assert not torch.equal(outs[0][0], outs[2][0])
+    lib.pg_destroy(ctx)
