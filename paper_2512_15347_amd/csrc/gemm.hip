@@ -131,14 +131,14 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
   if constexpr (DMA) {
     // ---- global -> LDS directly: every wave owns N_REG / WAVES regions of 1 KB (64 / CH tile rows) ----
     constexpr int WAVES = WM * WN, RPR = 64 / CH;
-    constexpr int A_REG = BM / RPR, N_REG = (BM + BN) / RPR, PER_WAVE = N_REG / WAVES;
-    static_assert(N_REG % WAVES == 0, "regions must divide among the waves");
+    constexpr int A_REG = BM / RPR, N_REG = (BM + BN) / RPR, PER_WAVE = (N_REG + WAVES - 1) / WAVES;
+    static_assert(NST == 2 || N_REG % WAVES == 0, "deeper pipelines count loads per wave: regions must divide evenly");
     const uint16_t* g_ptr[PER_WAVE];
     uint32_t g_lds[PER_WAVE];
     const uint32_t lds_base = (uint32_t)(uintptr_t)smem;
 #pragma unroll
     for (int i = 0; i < PER_WAVE; ++i) {
-      const int g = wave + i * WAVES;                 // wave-uniform region id
+      const int g = min(wave + i * WAVES, N_REG - 1);  // wave-uniform region id (the last wave may own one fewer)
       const bool is_w = g >= A_REG;
       const int rg = is_w ? g - A_REG : g;
       const int row = rg * RPR + lane / CH;
@@ -149,7 +149,8 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
     }
     auto issue = [&](int kt, int stage) {
 #pragma unroll
-      for (int i = 0; i < PER_WAVE; ++i) dma16(g_ptr[i] + kt * BK, g_lds[i] + stage * STAGE_BYTES);
+      for (int i = 0; i < PER_WAVE; ++i)
+        if (wave + i * WAVES < N_REG) dma16(g_ptr[i] + kt * BK, g_lds[i] + stage * STAGE_BYTES);
     };
     // NST stages in flight: tile kt+NST-1 is requested while tile kt is multiplied.  At the barrier of
     // iteration kt every wave has its share of tile kt in LDS (all but the loads of the NST-2 younger
@@ -177,7 +178,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
           if (more && ks - my_half == sl) {
 #pragma unroll
             for (int i = 0; i < PER_SLAB; ++i)
-              if (sl * PER_SLAB + i < PER_WAVE)
+              if (sl * PER_SLAB + i < PER_WAVE && wave + (sl * PER_SLAB + i) * WAVES < N_REG)
                 dma16(g_ptr[sl * PER_SLAB + i] + kn * BK, g_lds[sl * PER_SLAB + i] + nstage * STAGE_BYTES);
           }
         __builtin_amdgcn_sched_barrier(0);
@@ -257,11 +258,12 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
   if constexpr (EPI != EPI_UNPATCH) {
     // ---- row-major epilogues: transpose each 32-row slab of the wave tile through LDS so that a lane
     // owns 4 consecutive columns of a row and every global access is 16 bytes wide (8 for bf16) ----
-    static_assert(TN == 2, "the staged epilogue assumes 64 columns per wave");
+    static_assert(TN == 1 || TN == 2, "the staged epilogue handles 32 or 64 columns per wave");
+    constexpr int LPR = TN * 8, RPI = 64 / LPR, NP = 32 / RPI;   // lanes per row, rows per access, accesses per slab
     constexpr int EST = TN * 32 + 8;                 // staging row stride in floats (half-waves hit disjoint banks)
     __syncthreads();                                 // every wave has finished reading the last stage
     float* stg = reinterpret_cast<float*>(smem) + wave * (32 * EST);
-    const int c4 = (lane & 15) * 4, rsub = lane >> 4;
+    const int c4 = (lane % LPR) * 4, rsub = lane / LPR;
     const int n = n0 + wn * (BN / WN) + c4;
     const bool n_ok = n < a.N;                       // N is a multiple of 4
     float4 b4 = {0.f, 0.f, 0.f, 0.f};
@@ -280,10 +282,10 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
         for (int q = 0; q < 4; ++q)
 #pragma unroll
           for (int t = 0; t < 4; ++t) stg[(8 * q + 4 * half + t) * EST + j * 32 + l32] = acc[i][j][4 * q + t];
-      float4 v[8];
+      float4 v[NP];
 #pragma unroll
-      for (int p = 0; p < 8; ++p) {
-        v[p] = *reinterpret_cast<const float4*>(stg + (4 * p + rsub) * EST + c4);
+      for (int p = 0; p < NP; ++p) {
+        v[p] = *reinterpret_cast<const float4*>(stg + (RPI * p + rsub) * EST + c4);
         v[p].x += b4.x; v[p].y += b4.y; v[p].z += b4.z; v[p].w += b4.w;
       }
       if (EPI == EPI_RESID) {
@@ -298,10 +300,10 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
           g0 = *reinterpret_cast<const float4*>(a.gate + (int64_t)a.group_of[traj0] * a.gate_ld + n);
           g1 = *reinterpret_cast<const float4*>(a.gate + (int64_t)a.group_of[min(traj0 + 1, last)] * a.gate_ld + n);
         }
-        float4 hv[8], gv[8];
+        float4 hv[NP], gv[NP];
 #pragma unroll
-        for (int p = 0; p < 8; ++p) {
-          const int r = slab0 + 4 * p + rsub;
+        for (int p = 0; p < NP; ++p) {
+          const int r = slab0 + RPI * p + rsub;
           const bool ok = r < a.M && n_ok;
           hv[p] = ok ? *reinterpret_cast<const float4*>(a.outf + (int64_t)r * a.ldo + n) : float4{0.f, 0.f, 0.f, 0.f};
           gv[p] = r < split ? g0 : g1;
@@ -309,8 +311,8 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
             gv[p] = *reinterpret_cast<const float4*>(a.gate + (int64_t)a.group_of[r / a.L] * a.gate_ld + n);
         }
 #pragma unroll
-        for (int p = 0; p < 8; ++p) {
-          const int r = slab0 + 4 * p + rsub;
+        for (int p = 0; p < NP; ++p) {
+          const int r = slab0 + RPI * p + rsub;
           if (r < a.M && n_ok) {
             float4 o = {hv[p].x + gv[p].x * v[p].x, hv[p].y + gv[p].y * v[p].y, hv[p].z + gv[p].z * v[p].z,
                         hv[p].w + gv[p].w * v[p].w};
@@ -320,8 +322,8 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
         continue;
       }
 #pragma unroll
-      for (int p = 0; p < 8; ++p) {
-        const int r = slab0 + 4 * p + rsub;
+      for (int p = 0; p < NP; ++p) {
+        const int r = slab0 + RPI * p + rsub;
         if (r >= a.M || !n_ok) continue;
         if (EPI == EPI_F32) {
           *reinterpret_cast<float4*>(a.outf + (int64_t)r * a.ldo + n) = v[p];
@@ -400,17 +402,17 @@ static pg_status launch_tile(const GemmArgs& a, hipStream_t s) {
 // loop.  PROGRPO_GEMM_TILE (0..3) overrides the heuristic; it is a tuning aid.
 static int pick_tile(const GemmArgs& a) {
   static const int forced = [] { const char* e = getenv("PROGRPO_GEMM_TILE"); return e ? atoi(e) : -1; }();
-  if (forced >= 0 && forced <= 3) return forced;
+  if (forced >= 0 && forced <= 5) return forced;
   auto score = [&](int bm, int bn, int per_cu, double speed) {
     const double tiles = (double)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn);
     const double slots = 256.0 * per_cu;
     const double useful = (double)a.M * a.N / ((double)bm * bn);      // ragged edge tiles do less work
     return speed * useful / (ceil(tiles / slots) * slots);
   };
-  const double sc[4] = {score(256, 256, 1, 1.00), score(192, 256, 1, 0.97), score(128, 256, 1, 0.90),
-                        score(128, 128, 2, 0.85)};
+  const double sc[6] = {score(256, 256, 1, 1.00), score(192, 256, 1, 0.97), score(128, 256, 1, 0.90),
+                        score(128, 128, 2, 0.85), score(160, 256, 1, 0.92), score(224, 256, 1, 0.96)};
   int best = 0;
-  for (int i = 1; i < 4; ++i) if (sc[i] > sc[best] * 1.02) best = i;
+  for (int i = 1; i < 6; ++i) if (sc[i] > sc[best] * 1.02) best = i;
   return best;
 }
 
@@ -422,14 +424,17 @@ static pg_status launch_one(const GemmArgs& a, hipStream_t s) {
       case 0: return launch_tile<EPI, 256, 256, 64, 2, 4, 2, 2>(a, s);
       case 1: return launch_tile<EPI, 192, 256, 64, 2, 4, 2, 2>(a, s);
       case 2: return launch_tile<EPI, 128, 256, 64, 2, 4, 2, 2>(a, s);
-      default: return launch_tile<EPI, 128, 128, 64, 2, 2, 2, 2>(a, s);
+      case 3: return launch_tile<EPI, 128, 128, 64, 2, 2, 2, 2>(a, s);
+      case 4: return launch_tile<EPI, 160, 256, 64, 1, 8, 2, 2>(a, s);     // heights that are not a multiple of 64:
+      default: return launch_tile<EPI, 224, 256, 64, 1, 8, 2, 2>(a, s);    // one wave row, 32 columns per wave
     }
   }
   switch (pick_tile(a)) {      // PROGRPO_GEMM_STAGING=regs: staging through registers (tuning aid)
     case 0: return launch_tile<EPI, 256, 256, 64, 2, 4, 2, 0>(a, s);
     case 1: return launch_tile<EPI, 192, 256, 64, 2, 4, 2, 0>(a, s);
     case 2: return launch_tile<EPI, 128, 256, 64, 2, 4, 2, 0>(a, s);
-    default: return launch_tile<EPI, 128, 128, 64, 2, 2, 2, 0>(a, s);
+    case 3: return launch_tile<EPI, 128, 128, 64, 2, 2, 2, 0>(a, s);
+    default: return launch_tile<EPI, 256, 256, 64, 2, 4, 2, 0>(a, s);
   }
 }
 
