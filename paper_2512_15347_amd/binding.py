@@ -10,7 +10,7 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libprogrpo.so")
+LIB_PATH = os.environ.get("PROGRPO_LIB", os.path.join(_HERE, "libprogrpo.so"))
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(

@@ -72,13 +72,35 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;   // 32x32 MFMA tiles per wave
   constexpr int A_BYTES = BM * BK * 2, W_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + W_BYTES;
   constexpr int A_LD = BM * CH / THREADS, W_LD = BN * CH / THREADS;   // chunks staged per lane
-  constexpr bool TR = (EPI == EPI_VT);             // accumulate the transposed 32x32 tiles
   extern __shared__ __align__(16) unsigned char smem[];
-  // ---- which output tile: XCD-aware, banded raster ----
-  const int tiles_m = (a.M + BM - 1) / BM, tiles_n = (a.N + BN - 1) / BN;
-  const int total = tiles_m * tiles_n;
+  // ---- the problem this block works on.  Value channels (EPI_VT, and the columns >= v_start of
+  // EPI_QKV) are produced TRANSPOSED by swapping the operand roles: rows of the block's problem are
+  // the value channels n (operand "A" = their weight rows), its columns are the tokens (operand "W" =
+  // the activations), so that consecutive output columns are consecutive tokens of one row of V^T. ----
+  const uint16_t* PA = a.A; int64_t LDA = a.lda;
+  const uint16_t* PW = a.W; int64_t LDW = a.ldw;
+  const uint16_t* PB = a.bias;
+  int MM = a.M, NN = a.N;
+  bool vt_block = false;
   const int per_xcd = gridDim.x / XCDS;
-  const int b = a.raster ? (blockIdx.x % XCDS) * per_xcd + blockIdx.x / XCDS : blockIdx.x;
+  int b = a.raster ? (blockIdx.x % XCDS) * per_xcd + blockIdx.x / XCDS : blockIdx.x;
+  if (EPI == EPI_QKV || EPI == EPI_VT) {
+    const int vs = (EPI == EPI_VT) ? 0 : a.v_start;
+    const int tiles1 = ((a.M + BM - 1) / BM) * ((vs + BN - 1) / BN);
+    if (b < tiles1) {
+      NN = vs;
+    } else {
+      b -= tiles1;
+      vt_block = true;
+      PA = a.W + (int64_t)vs * a.ldw; LDA = a.ldw;
+      PW = a.A; LDW = a.lda;
+      PB = a.bias ? a.bias + vs : nullptr;
+      MM = a.N - vs; NN = a.M;
+    }
+  }
+  // ---- which output tile: XCD-aware, banded raster ----
+  const int tiles_m = (MM + BM - 1) / BM, tiles_n = (NN + BN - 1) / BN;
+  const int total = tiles_m * tiles_n;
   if (b >= total) return;
   const int band = a.group_m * tiles_n;
   const int first_m = (b / band) * a.group_m;
@@ -123,8 +145,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = TR ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], af[i], acc[i][j], 0, 0, 0)
-                         : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], wf[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], wf[j], acc[i][j], 0, 0, 0);
     }
   };
 
@@ -143,8 +164,8 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
       const int rg = is_w ? g - A_REG : g;
       const int row = rg * RPR + lane / CH;
       const int ch = (lane % CH) ^ swz<CH>(row);
-      g_ptr[i] = is_w ? a.W + (int64_t)min(n0 + row, a.N - 1) * a.ldw + ch * 8
-                      : a.A + (int64_t)min(m0 + row, a.M - 1) * a.lda + ch * 8;
+      g_ptr[i] = is_w ? PW + (int64_t)min(n0 + row, NN - 1) * LDW + ch * 8
+                      : PA + (int64_t)min(m0 + row, MM - 1) * LDA + ch * 8;
       g_lds[i] = __builtin_amdgcn_readfirstlane(lds_base + (is_w ? A_BYTES : 0) + rg * 1024);
     }
     auto issue = [&](int kt, int stage) {
@@ -193,13 +214,13 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
       const int c = tid + i * THREADS, row = c / CH, ch = c % CH;
-      a_ptr[i] = a.A + (int64_t)min(m0 + row, a.M - 1) * a.lda + ch * 8;
+      a_ptr[i] = PA + (int64_t)min(m0 + row, MM - 1) * LDA + ch * 8;
       a_st[i] = lds_off<CH>(row, ch);
     }
 #pragma unroll
     for (int i = 0; i < W_LD; ++i) {
       const int c = tid + i * THREADS, row = c / CH, ch = c % CH;
-      w_ptr[i] = a.W + (int64_t)min(n0 + row, a.N - 1) * a.ldw + ch * 8;
+      w_ptr[i] = PW + (int64_t)min(n0 + row, NN - 1) * LDW + ch * 8;
       w_st[i] = A_BYTES + lds_off<CH>(row, ch);
     }
     u32x4v ra[A_LD], rw[W_LD];
@@ -230,31 +251,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
     }
   }
 
-  // ---- epilogue: in each 32x32 tile a lane holds ONE column (l32) and rows 8q + 4*half + t ----
-  if (TR) {
-    // transposed tiles: accumulator rows are output columns n (value channels), its columns are tokens,
-    // so consecutive lanes write consecutive tokens of one row of V^T[traj][n][token]
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int r = m0 + wm * (BM / WM) + i * 32 + l32;
-      if (r >= a.M) continue;
-      const int traj = r / a.L, tok = r - traj * a.L;
-      uint16_t* vcol = a.vt + (int64_t)traj * a.N * a.Lpad + tok;
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            const int n = n0 + wn * (BN / WN) + j * 32 + 8 * q + 4 * half + t;
-            if (n < a.N) {
-              const float bv = a.bias ? bf16_to_f32(a.bias[n]) : 0.f;
-              vcol[(int64_t)n * a.Lpad] = f32_to_bf16(acc[i][j][4 * q + t] + bv);
-            }
-          }
-    }
-    return;
-  }
+  // ---- epilogue: in each 32x32 accumulator tile a lane holds ONE column (l32) and rows 8q + 4*half + t ----
   if constexpr (EPI != EPI_UNPATCH) {
     // ---- row-major epilogues: transpose each 32-row slab of the wave tile through LDS so that a lane
     // owns 4 consecutive columns of a row and every global access is 16 bytes wide (8 for bf16) ----
@@ -265,10 +262,54 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
     float* stg = reinterpret_cast<float*>(smem) + wave * (32 * EST);
     const int c4 = (lane % LPR) * 4, rsub = lane / LPR;
     const int n = n0 + wn * (BN / WN) + c4;
-    const bool n_ok = n < a.N;                       // N is a multiple of 4
+    if ((EPI == EPI_QKV || EPI == EPI_VT) && vt_block) {
+      // V^T[traj][channel][token]: rows of this block are channels, the lane's 4 columns are tokens
+      // n .. n+3; they are stored as two bf16 pairs when they sit in one trajectory at an even offset
+      const int Dv = MM;
+      const int traj0 = n / a.L, tok0 = n - traj0 * a.L;
+      const bool whole = n + 3 < NN && tok0 + 3 < a.L && (tok0 & 1) == 0;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int slab0 = m0 + wm * (BM / WM) + i * 32;
+        if (slab0 >= MM) break;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) stg[(8 * q + 4 * half + t) * EST + j * 32 + l32] = acc[i][j][4 * q + t];
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+          const int ch = slab0 + RPI * p + rsub;                 // value channel (row of the block)
+          float4 v = *reinterpret_cast<const float4*>(stg + (RPI * p + rsub) * EST + c4);
+          if (ch >= MM || n >= NN) continue;
+          const float bv = PB ? bf16_to_f32(PB[ch]) : 0.f;
+          v.x += bv; v.y += bv; v.z += bv; v.w += bv;
+          if (whole) {
+            uint32_t* dst = reinterpret_cast<uint32_t*>(a.vt + ((int64_t)traj0 * Dv + ch) * a.Lpad + tok0);
+            const uint2 pk = pack_bf16x4(v);
+            dst[0] = pk.x;
+            dst[1] = pk.y;
+          } else {
+            const float e[4] = {v.x, v.y, v.z, v.w};
+            int traj = traj0, tok = tok0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              if (n + k < NN) {
+                if (tok >= a.L) { tok -= a.L; ++traj; }
+                a.vt[((int64_t)traj * Dv + ch) * a.Lpad + tok] = f32_to_bf16(e[k]);
+                ++tok;
+              }
+            }
+          }
+        }
+      }
+      return;
+    }
+    const bool n_ok = n < NN;                        // N is a multiple of 4
     float4 b4 = {0.f, 0.f, 0.f, 0.f};
-    if (a.bias && n_ok) {
-      const uint2 raw = *reinterpret_cast<const uint2*>(a.bias + n);
+    if (PB && n_ok) {
+      const uint2 raw = *reinterpret_cast<const uint2*>(PB + n);
       b4 = {bf16_to_f32((uint16_t)raw.x), bf16_to_f32((uint16_t)(raw.x >> 16)), bf16_to_f32((uint16_t)raw.y),
             bf16_to_f32((uint16_t)(raw.y >> 16))};
     }
@@ -333,7 +374,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
           float4 o = {v[p].x + bf16_to_f32((uint16_t)raw.x), v[p].y + bf16_to_f32((uint16_t)(raw.x >> 16)),
                       v[p].z + bf16_to_f32((uint16_t)raw.y), v[p].w + bf16_to_f32((uint16_t)(raw.y >> 16))};
           *reinterpret_cast<float4*>(a.outf + ((int64_t)traj * a.L + tok) * a.ldo + n) = o;
-        } else if (EPI == EPI_BF16) {
+        } else if (EPI == EPI_BF16 || EPI == EPI_QKV) {
           *reinterpret_cast<uint2*>(a.outb + (int64_t)r * a.ldob + n) = pack_bf16x4(v[p]);
         } else if (EPI == EPI_GELU) {
           const float4 gl = {gelu_tanh(v[p].x), gelu_tanh(v[p].y), gelu_tanh(v[p].z), gelu_tanh(v[p].w)};
@@ -389,7 +430,11 @@ static pg_status launch_tile(const GemmArgs& a, hipStream_t s) {
                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS));
     attr_set = true;
   }
-  const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
+  int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
+  if (EPI == EPI_QKV || EPI == EPI_VT) {           // row-major part + role-swapped value part (see the kernel)
+    const int vs = (EPI == EPI_VT) ? 0 : a.v_start;
+    tiles = ((a.M + BM - 1) / BM) * ((vs + BN - 1) / BN) + ((a.N - vs + BM - 1) / BM) * ((a.M + BN - 1) / BN);
+  }
   const int grid = (tiles + XCDS - 1) / XCDS * XCDS;
   gemm_kernel<EPI, BM, BN, BK, WM, WN, MINW, NST><<<dim3(grid), dim3(64 * WM * WN), LDS, s>>>(a);
   PG_LAUNCH_CHECK("gemm_kernel");
@@ -448,24 +493,19 @@ pg_status launch_gemm(const GemmArgs& a_in, int epilogue, hipStream_t s) {
   if (a.lda % 8 || a.ldw % 8 || a.lda < a.K || a.ldw < a.K || ((uintptr_t)a.A & 15) || ((uintptr_t)a.W & 15))
     return fail(PG_ESHAPE, "GEMM operands need 16-byte aligned rows (lda %lld, ldw %lld)", (long long)a.lda, (long long)a.ldw);
   if (!a.A || !a.W) return fail(PG_EINVAL, "GEMM: null operand");
-  if (epilogue != EPI_UNPATCH && epilogue != EPI_VT && epilogue != EPI_QKV) {
+  if (epilogue != EPI_UNPATCH && epilogue != EPI_VT) {
     // the row-major epilogues write 4 consecutive columns per lane
-    if (a.N % 4) return fail(PG_ESHAPE, "GEMM N = %d must be a multiple of 4", a.N);
+    const int n_rm = epilogue == EPI_QKV ? a.v_start : a.N;
+    if (n_rm % 4) return fail(PG_ESHAPE, "GEMM N = %d must be a multiple of 4", n_rm);
     if ((a.outf && (a.ldo % 4 || ((uintptr_t)a.outf & 15))) || (a.outb && (a.ldob % 4 || ((uintptr_t)a.outb & 7))) ||
         (a.bias && ((uintptr_t)a.bias & 7)) || (a.gate && (a.gate_ld % 4 || ((uintptr_t)a.gate & 15))) ||
         (a.pos && ((uintptr_t)a.pos & 7)))
       return fail(PG_ESHAPE, "GEMM output / bias / gate rows need 16-byte (bf16: 8-byte) alignment");
   }
-  if (epilogue == EPI_QKV) {
-    // query | key columns row-major, value columns transposed: two launches over disjoint column ranges
-    GemmArgs qk = a;
-    qk.N = a.v_start;
-    PG_TRY(launch_gemm(qk, EPI_BF16, s));
-    GemmArgs v = a;
-    v.N = a.N - a.v_start;
-    v.W = a.W + (int64_t)a.v_start * a.ldw;
-    v.bias = a.bias ? a.bias + a.v_start : nullptr;
-    return launch_gemm(v, EPI_VT, s);
+  if (epilogue == EPI_QKV || epilogue == EPI_VT) {
+    if (!a.vt || a.L < 1 || a.Lpad < a.L || (a.Lpad & 1) || ((uintptr_t)a.vt & 3) ||
+        (epilogue == EPI_QKV && (a.v_start < 0 || a.v_start > a.N || !a.outb)))
+      return fail(PG_ESHAPE, "GEMM: bad transposed-value output (L %d, Lpad %d, v_start %d)", a.L, a.Lpad, a.v_start);
   }
   const int rec = prof_open(PROF_GEMM, 2.0 * a.M * (double)a.N * (a.k_algo > 0 ? a.k_algo : a.K), s);
   pg_status st = PG_EINVAL;
@@ -474,6 +514,7 @@ pg_status launch_gemm(const GemmArgs& a_in, int epilogue, hipStream_t s) {
     case EPI_EMBED: st = launch_one<EPI_EMBED>(a, s); break;
     case EPI_BF16: st = launch_one<EPI_BF16>(a, s); break;
     case EPI_VT: st = launch_one<EPI_VT>(a, s); break;
+    case EPI_QKV: st = launch_one<EPI_QKV>(a, s); break;
     case EPI_GELU: st = launch_one<EPI_GELU>(a, s); break;
     case EPI_RESID: st = launch_one<EPI_RESID>(a, s); break;
     case EPI_UNPATCH: st = launch_one<EPI_UNPATCH>(a, s); break;
