@@ -79,8 +79,23 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(const AttnArg
 #pragma unroll
   for (int i = 0; i < V_PER_THREAD; ++i) { const int cc = tid + i * ATT_THREADS; v_row[i] = cc >> 3; v_ch[i] = cc & 7; }
 
+  // staging sources for tile 0; full tiles advance them by whole tiles with wave-uniform offsets
+  const uint16_t* k_src[K_PER_THREAD];
+  const uint16_t* v_src[V_PER_THREAD];
+#pragma unroll
+  for (int i = 0; i < K_PER_THREAD; ++i) k_src[i] = kbase + (int64_t)min(k_row[i], a.Lk - 1) * a.ldk + k_ch[i] * 8;
+#pragma unroll
+  for (int i = 0; i < V_PER_THREAD; ++i) v_src[i] = vbase + (int64_t)v_row[i] * a.Lkpad + v_ch[i] * 8;
   auto load_tile = [&](int kt) {
     const int k0 = kt * KTILE;
+    if (k0 + KTILE <= a.Lk) {                    // full tile: no clamping, no masking
+      const int64_t koff = (int64_t)k0 * a.ldk;
+#pragma unroll
+      for (int i = 0; i < K_PER_THREAD; ++i) rk[i] = *reinterpret_cast<const u32x4v*>(k_src[i] + koff);
+#pragma unroll
+      for (int i = 0; i < V_PER_THREAD; ++i) rv[i] = *reinterpret_cast<const u32x4v*>(v_src[i] + k0);
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < K_PER_THREAD; ++i) {
       const int key = min(k0 + k_row[i], a.Lk - 1);
@@ -162,9 +177,10 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(const AttnArg
       for (int e = 0; e < 16; e += 2) {
         const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[t][e], c, neg_m));
         const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[t][e + 1], c, neg_m));
-        psum += p0 + p1;
         const f32x2v pp = {p0, p1};
         const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+        // the normaliser sums the probabilities as the value product sees them (rounded to bf16)
+        psum = __builtin_amdgcn_fdot2_f32_bf16(pb, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, psum, false);
         pf[t][e >> 3][e & 7] = pb[0];
         pf[t][e >> 3][(e & 7) + 1] = pb[1];
       }
