@@ -105,6 +105,8 @@ typedef struct pg_buffers {
   int32_t *status;         /* [4] device words: [0] = sticky error bits (1 = non-finite reward, 2 = bad k) */
   void *workspace;         /* pg_workspace_bytes() bytes, 256-byte aligned */
   size_t workspace_bytes;
+  float *x_hist;           /* optional (NULL: not kept) [T+1, M0, d] latents by ORIGINAL id: slice 0 = x_0,
+                              slice s+1 = state after step s (rows of trajectories pruned before step s are not written) */
 } pg_buffers;
 
 typedef struct pg_ctx pg_ctx;
@@ -166,6 +168,17 @@ pg_status pg_advantages(pg_ctx *ctx, void *stream);
 
 /* The whole loop: init, T x (network, prune at checkpoints, step), advantages. */
 pg_status pg_sample_group(pg_ctx *ctx, uint64_t seed, void *stream);
+
+/* Forward part of the policy update on the survivors (Sec. 5.1, Eq. 19 and the first term of Eq. 20): the
+ * stored transitions (x_s, x_{s+1}) of every surviving trajectory are re-evaluated under another weight set
+ * (`weights_new`, [device], same layout as pg_buffers.weights): logp_new[s, id] = log N(x_{s+1}; A_s x_s +
+ * B_s u_new(x_s, t_s), C_s^2 I), ratio[s, id] = exp(logp_new - logp_hist), and per group
+ * J[g] = mean over survivors and steps of min(r A, clip(r, 1 - clip_eps, 1 + clip_eps) A) with the advantages of
+ * pg_advantages.  logp_new, ratio: [device] [T, M0] by original id (NaN off the survivors); J: [device] [P].
+ * Needs pg_buffers.x_hist, a finished loop (all T steps and pg_advantages) and a network.  Overwrites the
+ * non-current x buffer and u.  The KL term of Eq. 20 (reference policy) is not computed. */
+pg_status pg_policy_ratio(pg_ctx *ctx, const uint16_t *weights_new, double clip_eps, float *logp_new,
+                          float *ratio, float *J, void *stream);
 
 /* Synchronises the stream and reports sticky device-side errors (PG_ENAN / PG_EINVAL). */
 pg_status pg_check(pg_ctx *ctx, void *stream);

@@ -50,7 +50,7 @@ class pg_buffers(C.Structure):
                 ("masks", C.c_void_p), ("sel_idx", C.c_void_p), ("logp_hist", C.c_void_p),
                 ("logp_sum", C.c_void_p), ("adv", C.c_void_p), ("probe_w", C.c_void_p),
                 ("weights", C.c_void_p), ("ctx", C.c_void_p), ("y", C.c_void_p), ("status", C.c_void_p),
-                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("x_hist", C.c_void_p)]
 
 
 class PgError(RuntimeError):
@@ -78,6 +78,7 @@ _SIGNATURES = {
     "pg_advantages": (_i32, [_vp, _vp]),
     "pg_sample_group": (_i32, [_vp, _u64, _vp]),
     "pg_check": (_i32, [_vp, _vp]),
+    "pg_policy_ratio": (_i32, [_vp, _vp, _f64, _vp, _vp, _vp, _vp]),
     "pg_init_latents": (_i32, [_vp, _vp, _i64, _i64, _u64, _vp]),
     "pg_step_scratch_floats": (_i64, [_i64, _i64]),
     "pg_sde_step_logprob": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _f64, _f64, _f64, _u64,
@@ -220,7 +221,7 @@ def pack_weights(ctx, cfg, weights):
 class Buffers:
     """Device tensors for one context (torch owns the memory) + the filled pg_buffers."""
 
-    def __init__(self, ctx, cfg, inputs=None, weights_flat=None, device="cuda:0"):
+    def __init__(self, ctx, cfg, inputs=None, weights_flat=None, device="cuda:0", keep_history=False):
         import torch
         P, N, T, d = cfg["P"], cfg["N"], cfg["T"], cfg["d"]
         M0 = P * N
@@ -262,6 +263,8 @@ class Buffers:
         b.y = _ptr(self.y)
         b.workspace = ws_ptr
         b.workspace_bytes = nbytes
+        self.x_hist = z(T + 1, M0, d) if keep_history else None
+        b.x_hist = _ptr(self.x_hist)
         self.c = b
 
 
@@ -303,6 +306,10 @@ def pg_advantages(ctx, stream=None):
 
 def pg_sample_group(ctx, seed, stream=None):
     _check(_lib.pg_sample_group(ctx, seed, _stream(stream)))
+
+
+def pg_policy_ratio(ctx, weights_new, clip_eps, logp_new, ratio, J, stream=None):
+    _check(_lib.pg_policy_ratio(ctx, _ptr(weights_new), clip_eps, _ptr(logp_new), _ptr(ratio), _ptr(J), _stream(stream)))
 
 
 def pg_check(ctx, stream=None):

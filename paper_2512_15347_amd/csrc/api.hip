@@ -378,7 +378,7 @@ extern "C" pg_status pg_init_group(pg_ctx* c, uint64_t seed, void* stream) {
   c->seed = seed;
   c->M = c->M0; c->cur_x = 0; c->cur_id = 0;
   c->pending_gather = false; c->net_fresh = false;
-  c->evals = 0; c->updates = 0;
+  c->evals = 0; c->updates = 0; c->steps_done = 0; c->advantages_done = false;
   int32_t* slot = c->staging + (size_t)f.T * (2 * f.P + 2);
   for (int g = 0; g <= f.P; ++g) { c->offsets[g] = g * f.N; slot[g] = g * f.N; }
   PG_HIP(hipMemcpyAsync(c->buf.group_offsets, slot, sizeof(int32_t) * (f.P + 1), hipMemcpyHostToDevice, s));
@@ -388,8 +388,10 @@ extern "C" pg_status pg_init_group(pg_ctx* c, uint64_t seed, void* stream) {
   PG_TRY(launch_fill_u32(c->buf.logp_sum, 0u, (size_t)c->M0, s));
   PG_TRY(launch_fill_u32(c->buf.status, 0u, 4, s));
   PG_TRY(pg_init_latents(c->buf.x[0], c->buf.orig_id[0], c->M0, c->d, seed, stream));
+  if (c->buf.x_hist)
+    PG_HIP(hipMemcpyAsync(c->buf.x_hist, c->buf.x[0], sizeof(float) * (size_t)c->M0 * c->d, hipMemcpyDeviceToDevice, s));
   if (f.net_kind != PG_NET_NONE && !c->context_ready) {
-    PG_TRY(net_prepare(c, s));
+    PG_TRY(net_prepare(c, c->buf.weights, s));
     c->context_ready = true;
   }
   c->initialised = true;
@@ -400,7 +402,8 @@ extern "C" pg_status pg_net_forward(pg_ctx* c, int32_t step, void* stream) {
   if (!c || !c->bound || !c->initialised) return fail(PG_ESCHED, "pg_net_forward: call pg_init_group first");
   if (step < 0 || step >= c->cfg.T) return fail(PG_EINVAL, "step %d out of range", step);
   if (c->pending_gather) return fail(PG_ESCHED, "pg_net_forward: a prune is waiting for its pg_step");
-  if (c->cfg.net_kind != PG_NET_NONE) PG_TRY(net_forward(c, step, (hipStream_t)stream));
+  if (c->cfg.net_kind != PG_NET_NONE)
+    PG_TRY(net_forward(c, step, c->buf.x[c->cur_x], c->buf.weights, (hipStream_t)stream));
   c->net_fresh = true;
   c->evals += c->M;
   return PG_OK;
@@ -491,11 +494,14 @@ extern "C" pg_status pg_step(pg_ctx* c, int32_t step, void* stream) {
   if (!c || !c->bound || !c->initialised) return fail(PG_ESCHED, "pg_step: call pg_init_group first");
   if (step < 0 || step >= c->cfg.T) return fail(PG_EINVAL, "step %d out of range", step);
   if (!c->net_fresh) return fail(PG_ESCHED, "pg_step: no network evaluation for the current latents");
-  PG_TRY(pg_sde_step_logprob(c->buf.x[c->cur_x], c->buf.u, c->buf.x[1 - c->cur_x], nullptr,
-                             c->buf.logp_hist + (size_t)step * c->M0, c->buf.logp_sum,
-                             c->pending_gather ? c->buf.sel_idx : nullptr, c->buf.orig_id[c->cur_id], c->M,
-                             c->d, c->A[step], c->B[step], c->C[step], c->seed, (uint32_t)step,
-                             (float*)ws(c, c->ws_partials), stream));
+  if (step != c->steps_done) return fail(PG_ESCHED, "pg_step: step %d out of order (next is %d)", step, c->steps_done);
+  float* hist_next = c->buf.x_hist ? c->buf.x_hist + (size_t)(step + 1) * c->M0 * c->d : nullptr;
+  PG_TRY(launch_sde_step(c->buf.x[c->cur_x], c->buf.u, c->buf.x[1 - c->cur_x], nullptr,
+                         c->buf.logp_hist + (size_t)step * c->M0, c->buf.logp_sum,
+                         c->pending_gather ? c->buf.sel_idx : nullptr, c->buf.orig_id[c->cur_id], c->M, c->d,
+                         c->A[step], c->B[step], c->C[step], c->seed, (uint32_t)step,
+                         (float*)ws(c, c->ws_partials), hist_next, (hipStream_t)stream));
+  c->steps_done = step + 1;
   c->cur_x = 1 - c->cur_x;
   c->pending_gather = false;
   c->net_fresh = false;
@@ -508,7 +514,39 @@ extern "C" pg_status pg_advantages(pg_ctx* c, void* stream) {
   if (c->pending_gather) return fail(PG_ESCHED, "pg_advantages: a prune is waiting for its pg_step");
   PG_TRY(pg_preview_reward(c->buf.x[c->cur_x], nullptr, c->buf.probe_w, c->buf.rewards, c->M, c->d, 1.0, 0.0,
                            c->cfg.probe_bias, (float*)ws(c, c->ws_partials), stream));
-  return pg_group_advantages(c->buf.rewards, c->buf.group_offsets, c->cfg.P, c->cfg.adv_eps, c->buf.adv, stream);
+  PG_TRY(pg_group_advantages(c->buf.rewards, c->buf.group_offsets, c->cfg.P, c->cfg.adv_eps, c->buf.adv, stream));
+  c->advantages_done = true;
+  return PG_OK;
+}
+
+extern "C" pg_status pg_policy_ratio(pg_ctx* c, const uint16_t* weights_new, double clip_eps, float* logp_new,
+                                     float* ratio, float* J, void* stream) {
+  if (!c || !c->bound || !c->initialised) return fail(PG_ESCHED, "pg_policy_ratio: call pg_init_group first");
+  const pg_config& f = c->cfg;
+  if (f.net_kind == PG_NET_NONE) return fail(PG_EINVAL, "pg_policy_ratio: the context has no network");
+  if (!c->buf.x_hist) return fail(PG_EINVAL, "pg_policy_ratio: pg_buffers.x_hist was not bound");
+  if (c->steps_done != f.T || !c->advantages_done || c->pending_gather)
+    return fail(PG_ESCHED, "pg_policy_ratio: the sampling loop has not finished (steps %d of %d)", c->steps_done, f.T);
+  if (!weights_new || !logp_new || !ratio || !J) return fail(PG_EINVAL, "pg_policy_ratio: null pointer");
+  if (((uintptr_t)weights_new & 15)) return fail(PG_ESHAPE, "pg_policy_ratio: weights must be 16-byte aligned");
+  if (!(clip_eps >= 0.0 && clip_eps < 1.0)) return fail(PG_EINVAL, "pg_policy_ratio: clip_eps = %g", clip_eps);
+  hipStream_t s = (hipStream_t)stream;
+  const size_t slice = (size_t)c->M0 * c->d;
+  float* xb = c->buf.x[1 - c->cur_x];                 // scratch batch: the survivors' state at step s
+  const int32_t* ids = c->buf.orig_id[c->cur_id];
+  PG_TRY(launch_fill_u32(logp_new, 0x7FC00000u, (size_t)f.T * c->M0, s));
+  PG_TRY(launch_fill_u32(ratio, 0x7FC00000u, (size_t)f.T * c->M0, s));
+  PG_TRY(net_prepare(c, weights_new, s));
+  c->context_ready = false;                           // the cached context projections now belong to weights_new
+  for (int t = 0; t < f.T; ++t) {
+    PG_TRY(pg_compact_gather(c->buf.x_hist + (size_t)t * slice, xb, ids, c->M, c->d, stream));
+    PG_TRY(net_forward(c, t, xb, weights_new, s));
+    PG_TRY(launch_transition_logprob(xb, c->buf.u, c->buf.x_hist + (size_t)(t + 1) * slice, ids, c->M, c->d, c->A[t],
+                                     c->B[t], c->C[t], logp_new + (size_t)t * c->M0, (float*)ws(c, c->ws_partials), s));
+  }
+  c->net_fresh = false;
+  return launch_surrogate(logp_new, c->buf.logp_hist, c->buf.adv, c->buf.group_offsets, ids, f.P, f.T, c->M0,
+                          clip_eps, ratio, J, s);
 }
 
 extern "C" pg_status pg_sample_group(pg_ctx* c, uint64_t seed, void* stream) {

@@ -31,6 +31,8 @@ struct pg_ctx {
   bool pending_gather = false, initialised = false, net_fresh = false;
   std::vector<int> offsets;               // host copy, P+1
   int64_t evals = 0, updates = 0;
+  int steps_done = 0;                     // steps taken since pg_init_group
+  bool advantages_done = false;
   bool context_ready = false;             // step-independent network precomputation done
   // pinned host staging for the per-checkpoint k / offsets uploads: [T][2P+2] ints
   int32_t* staging = nullptr;
@@ -39,8 +41,20 @@ struct pg_ctx {
 namespace pg {
 // network (dit_kernels.hip)
 pg_status net_plan(pg_ctx* c);                                  // fills c->net, returns bytes in net.total
-pg_status net_prepare(pg_ctx* c, hipStream_t s);                // step-independent precomputation
-pg_status net_forward(pg_ctx* c, int step, hipStream_t s);      // u = net(x[cur_x]) for the M active rows
+pg_status net_prepare(pg_ctx* c, const uint16_t* weights, hipStream_t s);   // step-independent precomputation
+// u = net(x) for the M active rows of `x` under `weights`
+pg_status net_forward(pg_ctx* c, int step, const float* x, const uint16_t* weights, hipStream_t s);
+// sampler_kernels.hip
+pg_status launch_sde_step(const float* x, const float* u, float* x_out, float* logp, float* logp_hist,
+                          float* logp_sum, const int32_t* src, const int32_t* orig_id, int64_t n_traj, int64_t d,
+                          double A, double B, double C, uint64_t seed, uint32_t step, float* partials,
+                          float* hist_next, hipStream_t s);
+pg_status launch_transition_logprob(const float* x, const float* u, const float* x_next_by_id,
+                                    const int32_t* orig_id, int64_t n_traj, int64_t d, double A, double B, double C,
+                                    float* logp_by_id, float* partials, hipStream_t s);
+pg_status launch_surrogate(const float* logp_new, const float* logp_old, const float* adv, const int32_t* offsets,
+                           const int32_t* orig_id, int n_groups, int T, int M0, double clip_eps, float* ratio,
+                           float* J, hipStream_t s);
 // small launches (ovf_kernels.hip)
 pg_status launch_fill_u32(void* p, uint32_t v, size_t n, hipStream_t s);
 pg_status launch_iota(int32_t* p, int n, hipStream_t s);

@@ -228,9 +228,9 @@ struct Net {
 }  // namespace
 
 // Step-independent work: projected context rows (joint) or per-block context keys / values (cross).
-pg_status net_prepare(pg_ctx* c, hipStream_t s) {
+pg_status net_prepare(pg_ctx* c, const uint16_t* weights, hipStream_t s) {
   const pg_config& f = c->cfg;
-  Net n{c, s, (char*)c->buf.workspace + c->ws_net, c->buf.weights};
+  Net n{c, s, (char*)c->buf.workspace + c->ws_net, weights};
   const int D = f.D;
   if (f.net_kind == PG_NET_JOINT) {
     GemmArgs g{};
@@ -252,9 +252,9 @@ pg_status net_prepare(pg_ctx* c, hipStream_t s) {
   return PG_OK;
 }
 
-pg_status net_forward(pg_ctx* c, int step, hipStream_t s) {
+pg_status net_forward(pg_ctx* c, int step, const float* x_in, const uint16_t* weights, hipStream_t s) {
   const pg_config& f = c->cfg;
-  Net n{c, s, (char*)c->buf.workspace + c->ws_net, c->buf.weights};
+  Net n{c, s, (char*)c->buf.workspace + c->ws_net, weights};
   const NetPlan& pl = c->net;
   const int D = f.D, M = c->M, L = c->L, Li = c->Li, P = f.P, hd = D / f.heads;
   const int R = M * L, Ri = M * Li;
@@ -300,7 +300,7 @@ pg_status net_forward(pg_ctx* c, int step, hipStream_t s) {
   // ---- patch embedding (+ position table), context rows ----
   {
     const int64_t total = (int64_t)M * (Kp / 4) * Li;
-    patchify_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(c->buf.x[c->cur_x], tok, M, f.C, f.H,
+    patchify_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(x_in, tok, M, f.C, f.H,
                                                                                 f.W, Kp);
     PG_LAUNCH_CHECK("patchify_kernel");
     GemmArgs g{};

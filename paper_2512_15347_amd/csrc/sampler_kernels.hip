@@ -6,7 +6,7 @@
 // trajectory and moves it with 16-byte accesses; per-trajectory sums are written as one partial per
 // workgroup and finished by a second tiny kernel in a fixed order (fp64), so results do not depend
 // on scheduling.
-#include "common.hpp"
+#include "ctx.hpp"
 #include "philox.hpp"
 
 namespace pg {
@@ -46,10 +46,12 @@ __global__ __launch_bounds__(STREAM_THREADS) void init_latents_kernel(
 __global__ __launch_bounds__(STREAM_THREADS) void sde_step_kernel(
     const float* __restrict__ x, const float* __restrict__ u, float* __restrict__ x_out,
     const int32_t* __restrict__ src, const int32_t* __restrict__ orig_id, int d4, int chunks, float A,
-    float B, float C, uint32_t k0, uint32_t k1, uint32_t step, float* __restrict__ partials) {
+    float B, float C, uint32_t k0, uint32_t k1, uint32_t step, float* __restrict__ partials,
+    float* __restrict__ hist_next) {
   const int r = blockIdx.x / chunks, c = blockIdx.x - r * chunks;
   const int q = src ? src[r] : r;
   const uint32_t id = (uint32_t)orig_id[r];
+  f32x4* hn = hist_next ? reinterpret_cast<f32x4*>(hist_next) + (size_t)id * d4 : nullptr;
   const f32x4* xq = reinterpret_cast<const f32x4*>(x) + (size_t)q * d4;
   const f32x4* uq = reinterpret_cast<const f32x4*>(u) + (size_t)q * d4;
   f32x4* xo = reinterpret_cast<f32x4*>(x_out) + (size_t)r * d4;
@@ -74,6 +76,7 @@ __global__ __launch_bounds__(STREAM_THREADS) void sde_step_kernel(
       o.z = A * xv[it].z + B * uv[it].z + C * z.z;
       o.w = A * xv[it].w + B * uv[it].w + C * z.w;
       __builtin_nontemporal_store(o, xo + e4[it]);
+      if (hn) __builtin_nontemporal_store(o, hn + e4[it]);      // trajectory record by original id
       acc += (z.x * z.x + z.y * z.y) + (z.z * z.z + z.w * z.w);
     }
   }
@@ -156,6 +159,69 @@ __global__ __launch_bounds__(STREAM_THREADS) void compact_gather_kernel(
     if (e4[it] < d4) __builtin_nontemporal_store(v[it], xo + e4[it]);
 }
 
+// partial of |x_next[id] - (A x + B u)|^2 per workgroup (stored transition under another network output)
+__global__ __launch_bounds__(STREAM_THREADS) void transition_sq_kernel(
+    const float* __restrict__ x, const float* __restrict__ u, const float* __restrict__ x_next_by_id,
+    const int32_t* __restrict__ orig_id, int d4, int chunks, float A, float B, float* __restrict__ partials) {
+  const int r = blockIdx.x / chunks, c = blockIdx.x - r * chunks;
+  const f32x4* xr = reinterpret_cast<const f32x4*>(x) + (size_t)r * d4;
+  const f32x4* ur = reinterpret_cast<const f32x4*>(u) + (size_t)r * d4;
+  const f32x4* nr = reinterpret_cast<const f32x4*>(x_next_by_id) + (size_t)orig_id[r] * d4;
+  float acc = 0.f;
+#pragma unroll
+  for (int it = 0; it < STREAM_ITERS; ++it) {
+    const int e4 = c * (STREAM_CHUNK / 4) + it * STREAM_THREADS + threadIdx.x;
+    if (e4 < d4) {
+      const f32x4 xv = __builtin_nontemporal_load(xr + e4), uv = __builtin_nontemporal_load(ur + e4);
+      const f32x4 nv = __builtin_nontemporal_load(nr + e4);
+      const float a0 = nv.x - (A * xv.x + B * uv.x), a1 = nv.y - (A * xv.y + B * uv.y);
+      const float a2 = nv.z - (A * xv.z + B * uv.z), a3 = nv.w - (A * xv.w + B * uv.w);
+      acc += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
+    }
+  }
+  const float t = block_sum_256(acc);
+  if (threadIdx.x == 0) partials[blockIdx.x] = t;
+}
+
+// logp[id] = -sum / (2 C^2) - d (ln C + 1/2 ln 2 pi)
+__global__ void transition_finish_kernel(const float* __restrict__ partials, int chunks, int n_traj, double inv_2c2,
+                                         double log_norm, const int32_t* __restrict__ orig_id,
+                                         float* __restrict__ logp_by_id) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= n_traj) return;
+  double s = 0.0;
+  for (int c = 0; c < chunks; ++c) s += (double)partials[(size_t)r * chunks + c];
+  logp_by_id[orig_id[r]] = (float)(-s * inv_2c2 - log_norm);
+}
+
+// Eq. 19 and the first term of Eq. 20 per group: one wave per group, lanes over survivors
+__global__ __launch_bounds__(256) void surrogate_kernel(const float* __restrict__ logp_new,
+                                                        const float* __restrict__ logp_old,
+                                                        const float* __restrict__ adv,
+                                                        const int32_t* __restrict__ offsets,
+                                                        const int32_t* __restrict__ orig_id, int n_groups, int T,
+                                                        int M0, float lo, float hi, float* __restrict__ ratio,
+                                                        float* __restrict__ J) {
+  const int wv = threadIdx.x / WAVE, lane = threadIdx.x & (WAVE - 1);
+  const int g = blockIdx.x * 4 + wv;
+  if (g >= n_groups) return;
+  const int b = offsets[g], e = offsets[g + 1];
+  double acc = 0.0;
+  for (int i = b + lane; i < e; i += WAVE) {
+    const int id = orig_id[i];
+    const double a = (double)adv[i];
+    for (int s = 0; s < T; ++s) {
+      const double r = exp((double)logp_new[(size_t)s * M0 + id] - (double)logp_old[(size_t)s * M0 + id]);
+      ratio[(size_t)s * M0 + id] = (float)r;
+      const double rc = fmin(fmax(r, (double)lo), (double)hi);
+      acc += fmin(r * a, rc * a);
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, WAVE);
+  if (lane == 0) J[g] = (e > b) ? (float)(acc / ((double)(e - b) * T)) : 0.f;
+}
+
 static pg_status check_stream_shape(int64_t n_traj, int64_t d) {
   if (n_traj < 0 || d <= 0) return fail(PG_EINVAL, "n_traj = %lld, d = %lld", (long long)n_traj, (long long)d);
   if (d % 4 != 0) return fail(PG_ESHAPE, "latent size d = %lld must be a multiple of 4", (long long)d);
@@ -185,28 +251,64 @@ extern "C" pg_status pg_init_latents(float* x, const int32_t* orig_id, int64_t n
   return PG_OK;
 }
 
-extern "C" pg_status pg_sde_step_logprob(const float* x, const float* u, float* x_out, float* logp,
-                                         float* logp_hist, float* logp_sum, const int32_t* src,
-                                         const int32_t* orig_id, int64_t n_traj, int64_t d, double A,
-                                         double B, double C, uint64_t seed, uint32_t step,
-                                         float* partials, void* stream) {
+namespace pg {
+pg_status launch_sde_step(const float* x, const float* u, float* x_out, float* logp, float* logp_hist,
+                          float* logp_sum, const int32_t* src, const int32_t* orig_id, int64_t n_traj, int64_t d,
+                          double A, double B, double C, uint64_t seed, uint32_t step, float* partials,
+                          float* hist_next, hipStream_t stream) {
   PG_TRY(check_stream_shape(n_traj, d));
   if (n_traj == 0) return PG_OK;
   if (!x || !u || !x_out || !orig_id || !partials) return fail(PG_EINVAL, "pg_sde_step_logprob: null pointer");
   if (x_out == x) return fail(PG_EINVAL, "pg_sde_step_logprob: x_out must not alias x");
   if (!(C > 0.0)) return fail(PG_EINVAL, "pg_sde_step_logprob: noise scale C = %g must be > 0", C);
   const int chunks = (int)chunks_per_traj(d);
-  const int rec = prof_open(PROF_SDE_STEP, 12.0 * (double)n_traj * (double)d, (hipStream_t)stream);
-  sde_step_kernel<<<dim3((unsigned)(n_traj * chunks)), dim3(STREAM_THREADS), 0, (hipStream_t)stream>>>(
+  const int rec = prof_open(PROF_SDE_STEP, 12.0 * (double)n_traj * (double)d, stream);
+  sde_step_kernel<<<dim3((unsigned)(n_traj * chunks)), dim3(STREAM_THREADS), 0, stream>>>(
       x, u, x_out, src, orig_id, (int)(d / 4), chunks, (float)A, (float)B, (float)C, (uint32_t)seed,
-      (uint32_t)(seed >> 32), step, partials);
-  prof_close(rec, (hipStream_t)stream);
+      (uint32_t)(seed >> 32), step, partials, hist_next);
+  prof_close(rec, stream);
   PG_LAUNCH_CHECK("sde_step_kernel");
   const double log_norm = (double)d * (log(C) + 0.5 * log(2.0 * M_PI));
-  logprob_finish_kernel<<<dim3((unsigned)((n_traj + 127) / 128)), dim3(128), 0, (hipStream_t)stream>>>(
+  logprob_finish_kernel<<<dim3((unsigned)((n_traj + 127) / 128)), dim3(128), 0, stream>>>(
       partials, chunks, (int)n_traj, log_norm, orig_id, logp, logp_hist, logp_sum);
   PG_LAUNCH_CHECK("logprob_finish_kernel");
   return PG_OK;
+}
+
+pg_status launch_transition_logprob(const float* x, const float* u, const float* x_next_by_id,
+                                    const int32_t* orig_id, int64_t n_traj, int64_t d, double A, double B, double C,
+                                    float* logp_by_id, float* partials, hipStream_t stream) {
+  PG_TRY(check_stream_shape(n_traj, d));
+  if (n_traj == 0) return PG_OK;
+  const int chunks = (int)chunks_per_traj(d);
+  transition_sq_kernel<<<dim3((unsigned)(n_traj * chunks)), dim3(STREAM_THREADS), 0, stream>>>(
+      x, u, x_next_by_id, orig_id, (int)(d / 4), chunks, (float)A, (float)B, partials);
+  PG_LAUNCH_CHECK("transition_sq_kernel");
+  transition_finish_kernel<<<dim3((unsigned)((n_traj + 127) / 128)), dim3(128), 0, stream>>>(
+      partials, chunks, (int)n_traj, 1.0 / (2.0 * C * C), (double)d * (log(C) + 0.5 * log(2.0 * M_PI)), orig_id,
+      logp_by_id);
+  PG_LAUNCH_CHECK("transition_finish_kernel");
+  return PG_OK;
+}
+
+pg_status launch_surrogate(const float* logp_new, const float* logp_old, const float* adv, const int32_t* offsets,
+                           const int32_t* orig_id, int n_groups, int T, int M0, double clip_eps, float* ratio,
+                           float* J, hipStream_t stream) {
+  surrogate_kernel<<<dim3((n_groups + 3) / 4), dim3(256), 0, stream>>>(
+      logp_new, logp_old, adv, offsets, orig_id, n_groups, T, M0, (float)(1.0 - clip_eps), (float)(1.0 + clip_eps),
+      ratio, J);
+  PG_LAUNCH_CHECK("surrogate_kernel");
+  return PG_OK;
+}
+}  // namespace pg
+
+extern "C" pg_status pg_sde_step_logprob(const float* x, const float* u, float* x_out, float* logp,
+                                         float* logp_hist, float* logp_sum, const int32_t* src,
+                                         const int32_t* orig_id, int64_t n_traj, int64_t d, double A,
+                                         double B, double C, uint64_t seed, uint32_t step,
+                                         float* partials, void* stream) {
+  return launch_sde_step(x, u, x_out, logp, logp_hist, logp_sum, src, orig_id, n_traj, d, A, B, C, seed, step,
+                         partials, nullptr, (hipStream_t)stream);
 }
 
 extern "C" pg_status pg_preview_reward(const float* x, const float* u, const float* w, float* rewards,

@@ -161,3 +161,13 @@ def stress_latent_rows(rows, d, seed=MASTER_SEED, stream=4100):
     for i, r in enumerate(rows):
         out[i] = np.random.default_rng([seed, stream, int(r)]).standard_normal(d, dtype=np.float32)
     return out
+
+
+def perturbed_weights(weights, rel=0.02, seed=MASTER_SEED + 17):
+    """A nearby weight set (every tensor plus rel * std-0.02 noise, rounded to bf16 again): stands in for
+    the policy after a small update when the stored transitions are re-evaluated."""
+    rng = np.random.default_rng([seed, 5000])
+    bump = lambda a: bf16_round(a + rel * 0.02 * rng.standard_normal(a.shape, dtype=np.float32))
+    out = {k: bump(v) for k, v in weights.items() if k != "blocks"}
+    out["blocks"] = [{k: bump(v) for k, v in blk.items()} for blk in weights["blocks"]]
+    return out

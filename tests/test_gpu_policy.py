@@ -1,0 +1,145 @@
+"""GPU parity of the trajectory record and of the importance-ratio / clipped-surrogate forward pass
+(Eq. 19, first term of Eq. 20) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import loop, policy, sampler
+from paper_2512_15347_amd import workloads
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def _setup(lib, name, seed):
+    cfg = workloads.get_config(name)
+    w = workloads.make_weights(cfg); inp = workloads.make_inputs(cfg, w)
+    s = cfg["sampler"]
+    tables = (sampler.flow_sde_tables(cfg["T"], s["a"]) if s["kind"] == "flow"
+              else sampler.ddim_sde_tables(cfg["T"], s["eta"], s["beta0"], s["beta1"], s["T_train"]))
+    rec = loop.run(cfg, tables, inp, seed, wts=w, keep_u_steps=range(cfg["T"]))
+    c, keep = lib.make_config(cfg, probe_bias=inp["probe_b"])
+    ctx = lib.pg_create(c)
+    buf = lib.Buffers(ctx, cfg, inputs=inp, weights_flat=lib.pack_weights(ctx, cfg, w), keep_history=True)
+    lib.pg_bind(ctx, buf)
+    lib.pg_sample_group(ctx, seed)
+    lib.pg_check(ctx)
+    return cfg, w, inp, tables, rec, ctx, buf
+
+
+def _dev_weights(lib, ctx, cfg, w):
+    return torch.from_numpy(lib.pack_weights(ctx, cfg, w).view(np.int16)).to(DEV)
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2_small", "cfg4_small"])
+def test_trajectory_record_and_policy_ratio(lib, name):
+    say(f"policy ratio {name}")
+    seed = 31
+    cfg, w, inp, tables, rec, ctx, buf = _setup(lib, name, seed)
+    P, N, T = cfg["P"], cfg["N"], cfg["T"]
+    M0 = P * N
+    ids = rec["orig_id"]
+    st = lib.pg_state(ctx, P)
+    np.testing.assert_array_equal(buf.orig_id[st["cur_id"]].cpu().numpy()[:st["M"]], ids)
+    # the record: slice 0 is the initial group, slice s+1 the state after step s, by original id
+    hist = buf.x_hist.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(hist[0] - rec["x_init"])) < 2e-5
+    for s in range(T):
+        sid, xs = rec["x_after"][s]
+        for k, i in enumerate(sid):
+            assert np.max(np.abs(hist[s + 1, i] - xs[k])) <= 2e-2 * np.max(np.abs(xs[k]))
+    final = buf.x[st["cur_x"]].cpu().numpy()[:st["M"]]
+    np.testing.assert_array_equal(buf.x_hist[T].cpu().numpy()[ids], final)
+
+    logp_new = torch.zeros(T, M0, device=DEV); ratio = torch.zeros(T, M0, device=DEV); J = torch.zeros(P, device=DEV)
+    # Conditioning: a step with policy std C sees the network output through B/C, and the fp32 state
+    # through 1/C.  The last DDIM step (C = 0.01, |B|/C = 72) turns bf16 network noise into O(1) changes
+    # of the log-ratio; float comparisons of the ratio are made on the steps with |B|/C <= 10 only.
+    Bc = np.abs(tables["B"]) / tables["C"]
+    good = np.nonzero(Bc <= 10.0)[0]
+    assert len(good) >= T - 1
+    d = cfg["d"]
+    # (a) the same weights: every ratio is 1 up to the fp32 rounding of the stored state,
+    #     |log r| <~ sqrt(d) ulp(x) / C, and the objective is the mean advantage (0)
+    lib.pg_policy_ratio(ctx, buf.weights, 0.2, logp_new, ratio, J)
+    torch.cuda.synchronize()
+    r = ratio.cpu().numpy().astype(np.float64)
+    assert np.isnan(np.delete(r, ids, axis=1)).all()
+    for s in range(T):
+        xmax = float(np.max(np.abs(hist[s + 1][ids])))
+        bound = 8 * np.sqrt(d) * 2.0 ** -23 * xmax / tables["C"][s] + 1e-3
+        assert np.max(np.abs(np.log(r[s, ids]))) < bound, (s, bound)
+    np.testing.assert_allclose(logp_new.cpu().numpy()[:, ids], buf.logp_hist.cpu().numpy()[:, ids], rtol=1e-4)
+    if len(good) == T:
+        assert np.max(np.abs(J.cpu().numpy())) < 2e-3
+    # (b) a nearby weight set, against the oracle on its own stored trajectories
+    w2 = workloads.perturbed_weights(w)
+    want = policy.policy_ratio(cfg, tables, inp, rec, w2, clip_eps=0.2)
+    lib.pg_policy_ratio(ctx, _dev_weights(lib, ctx, cfg, w2), 0.2, logp_new, ratio, J)
+    torch.cuda.synchronize()
+    lp = logp_new.cpu().numpy().astype(np.float64)
+    np.testing.assert_allclose(lp[:, ids], want["logp_new"][:, ids], rtol=1e-3)
+    r = ratio.cpu().numpy().astype(np.float64)
+    log_r = np.log(r[:, ids])
+    log_w = np.log(want["ratio"][:, ids])
+    assert np.max(np.abs(log_w[good])) > 1e-2                # the update is visible
+    for s_ in good:
+        # the bf16 network differs from the fp64 one by ~2.5e-3 rms of its output; through B/C and a sum
+        # over d noise terms that is a log-ratio error of about (|B|/C) sqrt(d) 2.5e-3 rms(u)
+        u_rms = float(np.sqrt(np.mean(rec["u"][s_][1] ** 2)))
+        tol = 4 * Bc[s_] * np.sqrt(d) * 2.5e-3 * u_rms + 1e-2
+        err = np.max(np.abs(log_r[s_] - log_w[s_]))
+        say(f"  step {s_}: log-ratio in {log_w[s_].min():.3f} .. {log_w[s_].max():.3f}, error {err:.2e} (tolerance {tol:.2e})")
+        assert err < tol
+    scale = max(np.max(np.abs(rec["adv"])), 1.0)
+    if len(good) == T and np.max(Bc) < 1.0:                  # well-conditioned everywhere: the objective itself
+        np.testing.assert_allclose(J.cpu().numpy(), want["J"], atol=5e-2 * scale)
+    # internal consistency of the objective with the ratios and advantages the library itself wrote
+    adv = buf.adv.cpu().numpy()[:st["M"]].astype(np.float64)
+    off = st["offsets"]
+    for g in range(P):
+        rg = r[:, ids[off[g]:off[g + 1]]]
+        ag = adv[off[g]:off[g + 1]][None, :]
+        own = np.mean(np.minimum(rg * ag, np.clip(rg, 0.8, 1.2) * ag))
+        assert abs(float(J[g].cpu()) - own) < 1e-4 * max(1.0, abs(own))
+    # the loop still works afterwards (context projections are rebuilt for the sampling weights)
+    lib.pg_sample_group(ctx, seed)
+    lib.pg_check(ctx)
+    assert torch.equal(buf.x[lib.pg_state(ctx, P)["cur_x"]][:st["M"]], torch.from_numpy(final).to(DEV))
+    lib.pg_destroy(ctx)
+
+
+def test_policy_ratio_call_order_and_arguments(lib):
+    cfg = workloads.get_config("cfg1")
+    w = workloads.make_weights(cfg); inp = workloads.make_inputs(cfg, w)
+    c, keep = lib.make_config(cfg, probe_bias=inp["probe_b"])
+    ctx = lib.pg_create(c)
+    flat = lib.pack_weights(ctx, cfg, w)
+    T, M0 = cfg["T"], cfg["N"]
+    out = [torch.zeros(T, M0, device=DEV), torch.zeros(T, M0, device=DEV), torch.zeros(1, device=DEV)]
+    plain = lib.Buffers(ctx, cfg, inputs=inp, weights_flat=flat)
+    lib.pg_bind(ctx, plain)
+    lib.pg_sample_group(ctx, 1)
+    with pytest.raises(lib.PgError):                          # no trajectory record bound
+        lib.pg_policy_ratio(ctx, plain.weights, 0.2, *out)
+    buf = lib.Buffers(ctx, cfg, inputs=inp, weights_flat=flat, keep_history=True)
+    lib.pg_bind(ctx, buf)
+    lib.pg_init_group(ctx, 1)
+    with pytest.raises(lib.PgError) as e:                     # loop not finished
+        lib.pg_policy_ratio(ctx, buf.weights, 0.2, *out)
+    assert e.value.status == lib.PG_ESCHED
+    lib.pg_net_forward(ctx, 0)
+    with pytest.raises(lib.PgError):                          # steps must come in order
+        lib.pg_step(ctx, 1)
+    lib.pg_sample_group(ctx, 1)
+    with pytest.raises(lib.PgError):
+        lib.pg_policy_ratio(ctx, buf.weights, 1.5, *out)      # clip range
+    with pytest.raises(lib.PgError):
+        lib.pg_policy_ratio(ctx, None, 0.2, *out)
+    lib.pg_policy_ratio(ctx, buf.weights, 0.2, *out)
+    lib.pg_check(ctx)
+    lib.pg_destroy(ctx)
