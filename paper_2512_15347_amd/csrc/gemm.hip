@@ -173,37 +173,47 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
       for (int i = 0; i < PER_WAVE; ++i)
         if (wave + i * WAVES < N_REG) dma16(g_ptr[i] + kt * BK, g_lds[i] + stage * STAGE_BYTES);
     };
-    // NST stages in flight: tile kt+NST-1 is requested while tile kt is multiplied.  At the barrier of
-    // iteration kt every wave has its share of tile kt in LDS (all but the loads of the NST-2 younger
-    // tiles have landed) and has finished reading stage (kt-1) % NST, which is the one refilled next.
-    // The requests of one wave are spread over half of the K step's MFMA slabs, and the two waves that
-    // share a SIMD (wave, wave + 4) use opposite halves: a wave waiting for the texture-address unit to
-    // take its request cannot issue MFMAs, its partner can.
-    constexpr int SLABS = BK / 16, HALF = SLABS / 2 > 0 ? SLABS / 2 : 1;
-    constexpr int PER_SLAB = (PER_WAVE + HALF - 1) / HALF;
-    const int my_half = __builtin_amdgcn_readfirstlane((SLABS >= 2) ? ((wave >> 2) & 1) * HALF : 0);
+    // Two stages.  Operand fragments are double buffered in registers and read one MFMA slab ahead,
+    // also across the K-step boundary: while the last slab of tile kt is multiplied, the barrier that
+    // publishes tile kt+1 is passed, tile kt+2 is requested into the stage just vacated, and the first
+    // slab of tile kt+1 is read, so neither the barrier nor the LDS latency is exposed.
+    static_assert(NST == 2, "the direct-load pipeline is written for two stages");
+    constexpr int SLABS = BK / 16;
+    static_assert(SLABS % 2 == 0, "fragment buffers alternate per slab");
+    bf16x8 af[2][TM], wf[2][TN];
+    auto fetch = [&](int stage, int ks, int buf) {
+      const unsigned char* sA = smem + stage * STAGE_BYTES;
+      const unsigned char* sW = sA + A_BYTES;
 #pragma unroll
-    for (int t = 0; t < NST - 1; ++t)
-      if (t < nk) issue(t, t);
+      for (int i = 0; i < TM; ++i) af[buf][i] = *reinterpret_cast<const bf16x8*>(sA + lds_off<CH>(a_row[i], 2 * ks + half));
+#pragma unroll
+      for (int j = 0; j < TN; ++j) wf[buf][j] = *reinterpret_cast<const bf16x8*>(sW + lds_off<CH>(w_row[j], 2 * ks + half));
+    };
+    issue(0, 0);
+    wait_dma<0>();
+    __syncthreads();
+    if (nk > 1) issue(1, 1);
+    fetch(0, 0, 0);
     for (int kt = 0; kt < nk; ++kt) {
-      if (kt + NST - 1 <= nk) wait_dma<PER_WAVE * (NST - 2)>();
-      else wait_dma<0>();                          // tail: fewer tiles are in flight than the steady state
-      __syncthreads();
-      const int kn = kt + NST - 1;
-      const bool more = kn < nk;
-      const int nstage = kn % NST;
-      multiply_stage(kt % NST, [&](int ks) {
+      const int cur = kt & 1;
+#pragma unroll
+      for (int ks = 0; ks < SLABS; ++ks) {
+        if (ks + 1 < SLABS) {
+          fetch(cur, ks + 1, (ks + 1) & 1);
+        } else if (kt + 1 < nk) {
+          // every read of stage `cur` has been issued; once they have returned the stage may be refilled
+          wait_dma<0>();                           // this wave's share of tile kt+1 has landed
+          __syncthreads();                         // ... and everybody's; stage `cur` is free
+          if (kt + 2 < nk) issue(kt + 2, cur);
+          fetch(cur ^ 1, 0, 0);
+        }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int sl = 0; sl < HALF; ++sl)
-          if (more && ks - my_half == sl) {
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int i = 0; i < PER_SLAB; ++i)
-              if (sl * PER_SLAB + i < PER_WAVE && wave + (sl * PER_SLAB + i) * WAVES < N_REG)
-                dma16(g_ptr[sl * PER_SLAB + i] + kn * BK, g_lds[sl * PER_SLAB + i] + nstage * STAGE_BYTES);
-          }
-        __builtin_amdgcn_sched_barrier(0);
-      });
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], wf[ks & 1][j], acc[i][j], 0, 0, 0);
+      }
     }
   } else {
     // ---- global -> registers -> LDS ----
