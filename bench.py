@@ -23,6 +23,8 @@ DESCRIPTIONS = {
     "cfg2": "diffusion-shaped group N=24->12 @ step 5 of 20 (DDIM eta=1), latent 4x64x64, DiT 1024 tok x 768 x 12 blocks, 77x768 cross-attention",
     "cfg3": "flow-shaped group N=48->32->16 @ steps 2,4 of 10, latent 16x64x64, DiT (1024+154) tok x 1536 x 24 blocks, joint attention",
     "cfg4": "8 prompts x N=48 (ragged 48->32->16, one group unpruned), cfg3 network, one packed batch",
+    "paper_std": "the paper's standard flow schedule N=48->24->12 @ steps 5,7 of 10 on the cfg3 network",
+    "paper_flash": "the paper's efficiency schedule N=24->16->12 @ steps 5,7 of 10 on the cfg3 network",
 }
 
 
@@ -88,6 +90,48 @@ def stream_kernels_at_stress_shape(pg, torch, n=1024, d=16 * 128 * 128, reps=10)
     return res
 
 
+def group_kernels_at_stress_shape(pg, torch, np, workloads, reps=10):
+    """Variance-maximising selection 64 -> 16 and group advantages over many clustered-reward groups: these are
+    issue/latency bound (4 bytes per reward), so the figure is groups per second, not a bandwidth fraction."""
+    dev = "cuda:0"
+    res = {}
+    for n_groups in (4096, 1 << 20):
+        n, k = 64, 16
+        if n_groups == 4096:
+            r = torch.from_numpy(workloads.stress_rewards(n_groups, n)).to(dev).reshape(-1)
+        else:  # same distribution drawn on the device (the host recipe would take seconds at this size)
+            g = torch.Generator(device=dev); g.manual_seed(251215347)
+            cl = torch.rand(n_groups * n, device=dev, generator=g) < 0.8
+            r = torch.where(cl, torch.randn(n_groups * n, device=dev, generator=g) * 0.05,
+                            torch.rand(n_groups * n, device=dev, generator=g) * 2 - 1)
+        offs = torch.arange(0, (n_groups + 1) * n, n, dtype=torch.int32, device=dev)
+        kk = torch.full((n_groups,), k, dtype=torch.int32, device=dev)
+        masks = torch.zeros(n_groups, dtype=torch.int64, device=dev)
+        sel = torch.zeros(n_groups * k, dtype=torch.int32, device=dev)
+        noffs = torch.zeros(n_groups + 1, dtype=torch.int32, device=dev)
+        status = torch.zeros(4, dtype=torch.int32, device=dev)
+        scratch = torch.zeros(pg.pg_ovf_scratch_ints(n_groups), dtype=torch.int32, device=dev)
+        adv = torch.zeros(n_groups * n, device=dev)
+
+        def timed(fn):
+            for _ in range(2):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            us = 1e3 * e0.elapsed_time(e1) / reps
+            return dict(us=round(us, 1), groups_per_s=round(n_groups / us * 1e6, 0))
+
+        res[f"ovf_select_{n_groups}x64_to_16"] = timed(
+            lambda: pg.pg_ovf_select(r, offs, kk, n_groups, masks, sel, noffs, status, scratch))
+        res[f"group_advantages_{n_groups}x64"] = timed(lambda: pg.pg_group_advantages(r, offs, n_groups, 1e-6, adv))
+    return res
+
+
 def recorded_gemm_traffic(workload):
     """HBM bytes per GEMM launch from the committed counter summary, or None when there is none for this
     workload or the kernel source has changed since the counters were taken."""
@@ -115,8 +159,8 @@ def workloads_evals(cfg):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg2", choices=sorted(DESCRIPTIONS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0, help="trajectories in the oracle sample (0 = auto)")
@@ -186,6 +230,7 @@ def main():
 
     # the HBM-bound kernels at the stress shape (1024 trajectories of 16x128x128 fp32), outside the timed region
     others.update(stream_kernels_at_stress_shape(pg, torch))
+    others.update(group_kernels_at_stress_shape(pg, torch, np, workloads))
 
     out = dict(metric="trajectory-steps/s and s per group (N->k pruned sampling), 1 GPU",
                value=round(evals * args.steps / dt, 3), unit="trajectory-steps/s", n_gpus=1, steps=args.steps,
@@ -196,7 +241,7 @@ def main():
                            trajectory_steps_per_group_batch=evals, groups=cfg["P"]),
                roofline=roofline, other_kernels=others)
     if not args.no_cpu_baseline:
-        budget = args.cpu_sample or {"cfg1": 8, "cfg2": 8, "cfg3": 1, "cfg4": 1}[args.workload]
+        budget = args.cpu_sample or {"cfg1": 8, "cfg2": 8}.get(args.workload, 1)
         out["cpu_baseline"] = cpu_baseline(cfg, w, inp, seed, budget)
     pg.pg_destroy(ctx)
     print(json.dumps(out), flush=True)

@@ -168,18 +168,25 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
                       : PA + (int64_t)min(m0 + row, MM - 1) * LDA + ch * 8;
       g_lds[i] = __builtin_amdgcn_readfirstlane(lds_base + (is_w ? A_BYTES : 0) + rg * 1024);
     }
-    auto issue = [&](int kt, int stage) {
-#pragma unroll
-      for (int i = 0; i < PER_WAVE; ++i)
-        if (wave + i * WAVES < N_REG) dma16(g_ptr[i] + kt * BK, g_lds[i] + stage * STAGE_BYTES);
+    // request region i of K tile `kt` (nothing past the last tile)
+    auto request = [&](int i, int kt) {
+      if (kt < nk && wave + i * WAVES < N_REG) dma16(g_ptr[i] + kt * BK, g_lds[i] + (kt % NST) * STAGE_BYTES);
     };
-    // Two stages.  Operand fragments are double buffered in registers and read one MFMA slab ahead,
-    // also across the K-step boundary: while the last slab of tile kt is multiplied, the barrier that
-    // publishes tile kt+1 is passed, tile kt+2 is requested into the stage just vacated, and the first
-    // slab of tile kt+1 is read, so neither the barrier nor the LDS latency is exposed.
-    static_assert(NST == 2, "the direct-load pipeline is written for two stages");
-    constexpr int SLABS = BK / 16;
+    // NST stages of BK columns; tile kt lives in stage kt % NST.  Per K step: SLABS MFMA slabs.  Operand
+    // fragments are double buffered in registers and read one slab ahead, also across the K-step
+    // boundary: at the last slab of tile kt every read of its stage has been issued, so the barrier that
+    // publishes tile kt+1 (and frees stage kt % NST) is passed before that slab's MFMAs, and the first
+    // slab of tile kt+1 is read while they run.  The requests for tile kt+NST are not issued in a burst
+    // (a wave's request waits for the texture path, which takes 1 KB every ~20 cycles, and the MFMAs
+    // queued behind it would wait too): they are spread between the MFMAs of the SPREAD slabs that
+    // follow the barrier, one request every few MFMAs.
+    constexpr int SLABS = BK / 16, MF = TM * TN;
     static_assert(SLABS % 2 == 0, "fragment buffers alternate per slab");
+    constexpr int SPREAD = NST == 2 ? 2 : SLABS;                     // slabs over which one tile's requests go
+    constexpr int RPS = (PER_WAVE + SPREAD - 1) / SPREAD;            // requests per slab
+    constexpr int EVERY = MF / RPS > 0 ? MF / RPS : 1;               // one request after every EVERY-th MFMA
+    static_assert(RPS <= MF, "more requests than MFMAs in a slab");
+    constexpr int LAG = (NST - 2) * PER_WAVE;                        // requests that may stay in flight at the barrier
     bf16x8 af[2][TM], wf[2][TN];
     auto fetch = [&](int stage, int ks, int buf) {
       const unsigned char* sA = smem + stage * STAGE_BYTES;
@@ -189,30 +196,46 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
 #pragma unroll
       for (int j = 0; j < TN; ++j) wf[buf][j] = *reinterpret_cast<const bf16x8*>(sW + lds_off<CH>(w_row[j], 2 * ks + half));
     };
-    issue(0, 0);
-    wait_dma<0>();
+    // prologue: tiles 0 .. NST-2 are requested, tile 0 awaited
+#pragma unroll
+    for (int t = 0; t < NST - 1; ++t)
+#pragma unroll
+      for (int i = 0; i < PER_WAVE; ++i) request(i, t);
+    if (nk >= NST - 1) wait_dma<LAG>(); else wait_dma<0>();
     __syncthreads();
-    if (nk > 1) issue(1, 1);
+#pragma unroll
+    for (int i = 0; i < RPS; ++i) request(i, NST - 1);               // the share that position 0 would have carried
     fetch(0, 0, 0);
+    // slab position p after a barrier: p = 0 is the last slab of the K step that passed it, p >= 1 are
+    // slabs p-1 of the next K step; position p carries requests [p RPS, (p+1) RPS) of the tile freed there
     for (int kt = 0; kt < nk; ++kt) {
-      const int cur = kt & 1;
+      const int cur = kt % NST;
 #pragma unroll
       for (int ks = 0; ks < SLABS; ++ks) {
         if (ks + 1 < SLABS) {
           fetch(cur, ks + 1, (ks + 1) & 1);
         } else if (kt + 1 < nk) {
-          // every read of stage `cur` has been issued; once they have returned the stage may be refilled
-          wait_dma<0>();                           // this wave's share of tile kt+1 has landed
-          __syncthreads();                         // ... and everybody's; stage `cur` is free
-          if (kt + 2 < nk) issue(kt + 2, cur);
-          fetch(cur ^ 1, 0, 0);
+          // tiles up to kt+NST-1 have been requested (fewer near the end: then wait for all)
+          if (kt + NST - 1 < nk) wait_dma<LAG>(); else wait_dma<0>();
+          __syncthreads();                         // tile kt+1 is visible; stage `cur` is free
+          fetch((kt + 1) % NST, 0, 0);
         }
+        const int pos = ks + 1 < SLABS ? ks + 1 : 0;                 // compile-time after unrolling
+        const int tile = ks + 1 < SLABS ? kt - 1 + NST : kt + NST;   // the tile whose stage was freed last
         __builtin_amdgcn_sched_barrier(0);
+        int q = 0;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-          for (int j = 0; j < TN; ++j)
+          for (int j = 0; j < TN; ++j) {
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], wf[ks & 1][j], acc[i][j], 0, 0, 0);
+            if (pos < SPREAD && q % EVERY == 0 && q / EVERY < RPS && pos * RPS + q / EVERY < PER_WAVE) {
+              __builtin_amdgcn_sched_barrier(0);
+              request(pos * RPS + q / EVERY, tile);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+            ++q;
+          }
       }
     }
   } else {

@@ -58,6 +58,25 @@ CONFIGS = {
     # the paper's own schedules (Sec. 6.1, experimental settings) on the small network
     "paper_std_small": dict(P=1, N=48, C=4, H=16, W=16, T=10, sampler=_flow(), kind="adaln",
                             D=128, blocks=2, heads=4, Lc=0, Dc=0, schedule=[[(5, 24), (7, 12)]]),
+    # efficiency variant: 24 -> 16 -> 12 (the checkpoint steps are taken to be those of the standard variant)
+    "paper_flash_small": dict(P=1, N=24, C=4, H=16, W=16, T=10, sampler=_flow(), kind="joint",
+                              D=128, blocks=2, heads=2, Lc=26, Dc=128, schedule=[[(5, 16), (7, 12)]]),
+    # diffusion-model schedule: 48 -> 32 -> 8 at steps 30 and 40 of T = 50
+    "paper_diffusion_small": dict(P=1, N=48, C=4, H=8, W=8, T=50, sampler=_ddim(), kind="cross",
+                                  D=64, blocks=1, heads=1, Lc=13, Dc=64, schedule=[[(30, 32), (40, 8)]]),
+    # group-size ablation (Sec. 6.3): 32, 48 and 64 expanded trajectories pruned to 8; the intermediate size
+    # halves at the standard checkpoints (the paper prints only the two ends)
+    "paper_ablation32_small": dict(P=1, N=32, C=4, H=16, W=16, T=10, sampler=_flow(), kind="adaln",
+                                   D=128, blocks=2, heads=4, Lc=0, Dc=0, schedule=[[(5, 16), (7, 8)]]),
+    "paper_ablation48_small": dict(P=1, N=48, C=4, H=16, W=16, T=10, sampler=_flow(), kind="adaln",
+                                   D=128, blocks=2, heads=4, Lc=0, Dc=0, schedule=[[(5, 24), (7, 8)]]),
+    "paper_ablation64_small": dict(P=1, N=64, C=4, H=16, W=16, T=10, sampler=_flow(), kind="adaln",
+                                   D=128, blocks=2, heads=4, Lc=0, Dc=0, schedule=[[(5, 32), (7, 8)]]),
+    # the same schedules at the size of the flow-model benchmark network (bench.py workloads)
+    "paper_std": dict(P=1, N=48, C=16, H=64, W=64, T=10, sampler=_flow(), kind="joint",
+                      D=1536, blocks=24, heads=24, Lc=154, Dc=1536, schedule=[[(5, 24), (7, 12)]]),
+    "paper_flash": dict(P=1, N=24, C=16, H=64, W=64, T=10, sampler=_flow(), kind="joint",
+                        D=1536, blocks=24, heads=24, Lc=154, Dc=1536, schedule=[[(5, 16), (7, 12)]]),
 }
 
 

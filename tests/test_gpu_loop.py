@@ -232,13 +232,25 @@ def test_forced_masks_follow_the_oracle(lib):
     lib.pg_destroy(ctx)
 
 
-def test_paper_schedule_48_24_12_at_steps_5_7(lib):
-    """The paper's own flow schedule (Sec. 6.1: G_max = 48 pruned to 24 and 12 at steps 5 and 7 of T = 10)
-    on the small network: free-running library against the free-running oracle."""
-    name, seed = "paper_std_small", 2512
+PAPER_SCHEDULES = {
+    "paper_std_small": [48] * 6 + [24] * 2 + [12] * 2,
+    "paper_flash_small": [24] * 6 + [16] * 2 + [12] * 2,
+    "paper_diffusion_small": [48] * 31 + [32] * 10 + [8] * 9,
+    "paper_ablation32_small": [32] * 6 + [16] * 2 + [8] * 2,
+    "paper_ablation48_small": [48] * 6 + [24] * 2 + [8] * 2,
+    "paper_ablation64_small": [64] * 6 + [32] * 2 + [8] * 2,
+}
+
+
+@pytest.mark.parametrize("name", sorted(PAPER_SCHEDULES))
+def test_paper_schedules(lib, name):
+    """The paper's own schedules (Sec. 6.1: 48 -> 24 -> 12 at steps 5 and 7 of T = 10, the 24 -> 16 -> 12
+    efficiency variant, 48 -> 32 -> 8 at steps 30 and 40 of T = 50 for the diffusion model; Sec. 6.3: 32, 48
+    and 64 pruned to 8) on small networks: free-running library against the free-running oracle."""
+    seed = 2512
     say(f"full loop {name}")
     cfg, w, inp, tables, rec = _oracle(name, seed)
-    assert rec["active"] == [48] * 6 + [24] * 2 + [12] * 2
+    assert rec["active"] == PAPER_SCHEDULES[name]
     ctx, buf = _gpu_ctx(lib, cfg, w, inp)
     lib.pg_sample_group(ctx, seed)
     lib.pg_check(ctx)
