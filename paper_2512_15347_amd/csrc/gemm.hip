@@ -1,12 +1,15 @@
 // bf16 MFMA GEMM for gfx950: C[M, N] = A[M, K] W[N, K]^T with a fused epilogue.  This is where the
 // network evaluation of every denoising step spends its time (the noise-prediction row of the paper's
 // cost table, Sec. 6.2).  Built around the 32x32x16 bf16 MFMA:
-//   both operands are K-contiguous and staged global -> registers -> LDS in 16-byte chunks with two LDS
-//   stages; the loads of tile kt+2 are in flight while tile kt is multiplied and tile kt+1 is written
-//   to LDS at the top of the iteration, one barrier per K step; chunk positions are XOR-swizzled so
-//   that both the 16-byte staging writes and the 16-byte MFMA operand reads are bank-conflict free;
-//   workgroup ids are spread so that the tiles resident on one XCD (one L2) form a compact block of
-//   the output and share operand panels.
+//   both operands are K-contiguous; 16-byte chunks go from global memory straight into LDS (no register
+//   staging), two LDS stages of BK = 64 columns, one barrier per K step; the requests for tile kt+2 are
+//   interleaved with the MFMAs that follow the barrier instead of being issued in a burst; operand
+//   fragments are double buffered in registers and read one MFMA slab ahead, also across the barrier;
+//   chunk positions are XOR-swizzled so that the 16-byte operand reads are bank-conflict free while the
+//   direct loads still write 1 KB contiguous per instruction;
+//   the epilogue goes through an LDS transpose so that every lane stores 16 contiguous bytes, with the
+//   non-temporal hint; workgroup ids are spread so that the tiles resident on one XCD (one L2) form a
+//   compact block of the output and share operand panels.
 // Several tile shapes are instantiated (workgroup tile BM x BN x BK, WM x WN wavefronts); the launcher
 // picks one from the number of output tiles relative to the 256 compute units.
 #include <cmath>
@@ -42,6 +45,36 @@ template <int N>
 __device__ __forceinline__ void wait_dma() {
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+// Outputs are written, and the residual stream is read, once per launch: they go through the caches
+// with the non-temporal hint so that the operand panels shared by the tiles of an XCD stay resident.
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
+#ifndef PG_GEMM_STREAM
+#define PG_GEMM_STREAM 1
+#endif
+__device__ __forceinline__ void store_stream(float* p, const float4 v) {
+#if PG_GEMM_STREAM
+  __builtin_nontemporal_store(f32x4v{v.x, v.y, v.z, v.w}, reinterpret_cast<f32x4v*>(p));
+#else
+  *reinterpret_cast<float4*>(p) = v;
+#endif
+}
+__device__ __forceinline__ void store_stream(uint16_t* p, const uint2 v) {
+#if PG_GEMM_STREAM
+  __builtin_nontemporal_store(u32x2v{v.x, v.y}, reinterpret_cast<u32x2v*>(p));
+#else
+  *reinterpret_cast<uint2*>(p) = v;
+#endif
+}
+__device__ __forceinline__ float4 load_stream(const float* p) {
+#if PG_GEMM_STREAM
+  const f32x4v v = __builtin_nontemporal_load(reinterpret_cast<const f32x4v*>(p));
+  return float4{v[0], v[1], v[2], v[3]};
+#else
+  return *reinterpret_cast<const float4*>(p);
+#endif
 }
 
 // gelu_tanh(x) = x/2 (1 + tanh(y)) = x / (1 + exp(-2y)),  y = sqrt(2/pi) (x + 0.044715 x^3);
@@ -379,7 +412,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
         for (int p = 0; p < NP; ++p) {
           const int r = slab0 + RPI * p + rsub;
           const bool ok = r < a.M && n_ok;
-          hv[p] = ok ? *reinterpret_cast<const float4*>(a.outf + (int64_t)r * a.ldo + n) : float4{0.f, 0.f, 0.f, 0.f};
+          hv[p] = ok ? load_stream(a.outf + (int64_t)r * a.ldo + n) : float4{0.f, 0.f, 0.f, 0.f};
           gv[p] = r < split ? g0 : g1;
           if (a.gate && !fast && ok)
             gv[p] = *reinterpret_cast<const float4*>(a.gate + (int64_t)a.group_of[r / a.L] * a.gate_ld + n);
@@ -390,7 +423,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
           if (r < a.M && n_ok) {
             float4 o = {hv[p].x + gv[p].x * v[p].x, hv[p].y + gv[p].y * v[p].y, hv[p].z + gv[p].z * v[p].z,
                         hv[p].w + gv[p].w * v[p].w};
-            *reinterpret_cast<float4*>(a.outf + (int64_t)r * a.ldo + n) = o;
+            store_stream(a.outf + (int64_t)r * a.ldo + n, o);
           }
         }
         continue;
@@ -400,18 +433,18 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
         const int r = slab0 + RPI * p + rsub;
         if (r >= a.M || !n_ok) continue;
         if (EPI == EPI_F32) {
-          *reinterpret_cast<float4*>(a.outf + (int64_t)r * a.ldo + n) = v[p];
+          store_stream(a.outf + (int64_t)r * a.ldo + n, v[p]);
         } else if (EPI == EPI_EMBED) {
           const int traj = r / a.Li, tok = r - traj * a.Li;
           const uint2 raw = *reinterpret_cast<const uint2*>(a.pos + (int64_t)tok * a.N + n);
           float4 o = {v[p].x + bf16_to_f32((uint16_t)raw.x), v[p].y + bf16_to_f32((uint16_t)(raw.x >> 16)),
                       v[p].z + bf16_to_f32((uint16_t)raw.y), v[p].w + bf16_to_f32((uint16_t)(raw.y >> 16))};
-          *reinterpret_cast<float4*>(a.outf + ((int64_t)traj * a.L + tok) * a.ldo + n) = o;
+          store_stream(a.outf + ((int64_t)traj * a.L + tok) * a.ldo + n, o);
         } else if (EPI == EPI_BF16 || EPI == EPI_QKV) {
-          *reinterpret_cast<uint2*>(a.outb + (int64_t)r * a.ldob + n) = pack_bf16x4(v[p]);
+          store_stream(a.outb + (int64_t)r * a.ldob + n, pack_bf16x4(v[p]));
         } else if (EPI == EPI_GELU) {
           const float4 gl = {gelu_tanh(v[p].x), gelu_tanh(v[p].y), gelu_tanh(v[p].z), gelu_tanh(v[p].w)};
-          *reinterpret_cast<uint2*>(a.outb + (int64_t)r * a.ldob + n) = pack_bf16x4(gl);
+          store_stream(a.outb + (int64_t)r * a.ldob + n, pack_bf16x4(gl));
         }
       }
     }
