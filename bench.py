@@ -132,6 +132,49 @@ def group_kernels_at_stress_shape(pg, torch, np, workloads, reps=10):
     return res
 
 
+def comparison_arms(pg, torch, workloads, cfg, w, inp, seed, inloop_ctx, inloop_buf):
+    """Within-group reward spread of the paper's comparison arms (Sec. 4.1-4.2) on this workload: the full
+    expanded group, a uniform k-subset, OVF applied once after sampling, and the in-loop pruned survivors.
+    sigma_G and the share of members within one sigma of the mean, averaged over groups, plus the wall time
+    of sampling the full group (what the static arms pay) next to the pruned loop."""
+    import copy
+    import time
+    P = cfg["P"]
+    k_final = [sched[-1][1] if sched else cfg["N"] for sched in cfg["schedule"]]
+    full = copy.deepcopy(cfg)
+    full["schedule"] = [[] for _ in range(P)]
+    c, keep = pg.make_config(full, probe_bias=inp["probe_b"])
+    ctx = pg.pg_create(c)
+    buf = pg.Buffers(ctx, full, inputs=inp, weights_flat=pg.pack_weights(ctx, full, w))
+    pg.pg_bind(ctx, buf)
+    sig = torch.zeros(P, device="cuda:0"); share = torch.zeros(P, device="cuda:0")
+
+    def stats(b):
+        pg.pg_group_stats(b.rewards, b.group_offsets, P, 1.0, sig, share)
+        torch.cuda.synchronize()
+        return dict(sigma_G=round(float(sig.mean()), 6), share_within_1_sigma=round(float(share.mean()), 4))
+
+    out = {}
+    pg.pg_sample_group(ctx, seed)                       # warm-up of this context
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    pg.pg_sample_group(ctx, seed)
+    torch.cuda.synchronize()
+    out["full_group_s_per_group"] = round((time.perf_counter() - t0) / P, 6)
+    out["full_group"] = dict(members=cfg["N"], **stats(buf))
+    pg.pg_select_final(ctx, pg.SELECT_UNIFORM, k_final, 0)
+    out["uniform_subset"] = dict(members=k_final[0], **stats(buf))
+    pg.pg_sample_group(ctx, seed)
+    pg.pg_select_final(ctx, pg.SELECT_OVF, k_final, 0)
+    out["ovf_after_sampling"] = dict(members=k_final[0], **stats(buf))
+    pg.pg_check(ctx)
+    pg.pg_destroy(ctx)
+    pg.pg_sample_group(inloop_ctx, seed)
+    out["ovf_in_loop"] = dict(members=k_final[0], **stats(inloop_buf))
+    pg.pg_check(inloop_ctx)
+    return out
+
+
 def recorded_gemm_traffic(workload):
     """HBM bytes per GEMM launch from the committed counter summary, or None when there is none for this
     workload or the kernel source has changed since the counters were taken."""
@@ -163,6 +206,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg2", choices=sorted(DESCRIPTIONS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-arms", action="store_true", help="skip the comparison arms (full group, uniform subset, static OVF)")
     ap.add_argument("--cpu-sample", type=int, default=0, help="trajectories in the oracle sample (0 = auto)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -240,6 +284,8 @@ def main():
                config=dict(workload=f"{args.workload}: {DESCRIPTIONS[args.workload]}",
                            trajectory_steps_per_group_batch=evals, groups=cfg["P"]),
                roofline=roofline, other_kernels=others)
+    if not args.no_arms:
+        out["comparison_arms"] = comparison_arms(pg, torch, workloads, cfg, w, inp, seed, ctx, buf)
     if not args.no_cpu_baseline:
         budget = args.cpu_sample or {"cfg1": 8, "cfg2": 8}.get(args.workload, 1)
         out["cpu_baseline"] = cpu_baseline(cfg, w, inp, seed, budget)

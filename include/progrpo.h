@@ -169,6 +169,15 @@ pg_status pg_advantages(pg_ctx *ctx, void *stream);
 /* The whole loop: init, T x (network, prune at checkpoints, step), advantages. */
 pg_status pg_sample_group(pg_ctx *ctx, uint64_t seed, void *stream);
 
+/* Comparison arms of Sec. 4.1-4.2 on a finished run (after pg_advantages): select on the FINAL
+ * rewards, mode 0 = Optimal Variance Filtering applied once after sampling (Eq. 10), mode 1 = a
+ * uniformly random subset (pg_uniform_select with the run's seed and `draw`); k_per_group: [host] P
+ * ints, 1 <= k <= current group size.  The kept trajectories are packed (latents into the other
+ * x buffer, ids, rewards, group offsets), masks / sel_idx hold the selection, and Eq. 18 is
+ * recomputed on the kept members.  Asynchronous on `stream`. */
+pg_status pg_select_final(pg_ctx *ctx, int32_t mode, const int32_t *k_per_group, uint32_t draw,
+                          void *stream);
+
 /* Forward part of the policy update on the survivors (Sec. 5.1, Eq. 19 and the first term of Eq. 20): the
  * stored transitions (x_s, x_{s+1}) of every surviving trajectory are re-evaluated under another weight set
  * (`weights_new`, [device], same layout as pg_buffers.weights): logp_new[s, id] = log N(x_{s+1}; A_s x_s +
@@ -219,6 +228,21 @@ int64_t pg_ovf_scratch_ints(int64_t n_groups);
 pg_status pg_ovf_select(const float *rewards, const int32_t *group_offsets, const int32_t *k,
                         int32_t n_groups, uint64_t *masks, int32_t *sel_idx, int32_t *new_offsets,
                         int32_t *status, int32_t *scratch, void *stream);
+
+/* Uniformly random k-subset per ragged group (the subsampling arm of Sec. 4.1), same outputs and
+ * status convention as pg_ovf_select.  Slot j of group g draws one 32-bit key, word 0 of the
+ * Philox-4x32-10 block with counter (j, draw, g, 2) and key (seed low, seed high); the k[g] slots
+ * with the smallest (key, slot) are kept. */
+pg_status pg_uniform_select(const int32_t *group_offsets, const int32_t *k, int32_t n_groups,
+                            uint64_t seed, uint32_t draw, uint64_t *masks, int32_t *sel_idx,
+                            int32_t *new_offsets, int32_t *status, int32_t *scratch, void *stream);
+
+/* Group diagnostics of Sec. 4.1 per ragged group (any size): sigma[g] = population standard
+ * deviation of the group's rewards (fp64 inside), clustered_share[g] = share of members with
+ * |R - mean| <= delta * sigma (the region C_delta of Eq. 7).  Either output may be NULL; an empty
+ * group reports 0, 0. */
+pg_status pg_group_stats(const float *rewards, const int32_t *group_offsets, int32_t n_groups,
+                         double delta, float *sigma, float *clustered_share, void *stream);
 
 /* out[r, :] = x[src[r], :] for r < n_out (ragged survivor compaction); out must not alias x;
  * d multiple of 4. */

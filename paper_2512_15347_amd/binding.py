@@ -79,6 +79,7 @@ _SIGNATURES = {
     "pg_sample_group": (_i32, [_vp, _u64, _vp]),
     "pg_check": (_i32, [_vp, _vp]),
     "pg_policy_ratio": (_i32, [_vp, _vp, _f64, _vp, _vp, _vp, _vp]),
+    "pg_select_final": (_i32, [_vp, _i32, _ip, _u32, _vp]),
     "pg_init_latents": (_i32, [_vp, _vp, _i64, _i64, _u64, _vp]),
     "pg_step_scratch_floats": (_i64, [_i64, _i64]),
     "pg_sde_step_logprob": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _f64, _f64, _f64, _u64,
@@ -86,6 +87,8 @@ _SIGNATURES = {
     "pg_preview_reward": (_i32, [_vp, _vp, _vp, _vp, _i64, _i64, _f64, _f64, _f64, _vp, _vp]),
     "pg_ovf_scratch_ints": (_i64, [_i64]),
     "pg_ovf_select": (_i32, [_vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "pg_uniform_select": (_i32, [_vp, _vp, _i32, _u64, _u32, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "pg_group_stats": (_i32, [_vp, _vp, _i32, _f64, _vp, _vp, _vp]),
     "pg_compact_gather": (_i32, [_vp, _vp, _vp, _i64, _i64, _vp]),
     "pg_group_advantages": (_i32, [_vp, _vp, _i32, _f64, _vp, _vp]),
     "pg_gemm_bf16": (_i32, [_vp, _i64, _vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _vp]),
@@ -308,6 +311,14 @@ def pg_sample_group(ctx, seed, stream=None):
     _check(_lib.pg_sample_group(ctx, seed, _stream(stream)))
 
 
+SELECT_OVF, SELECT_UNIFORM = 0, 1
+
+
+def pg_select_final(ctx, mode, k_per_group, draw=0, stream=None):
+    k = (C.c_int32 * len(k_per_group))(*[int(v) for v in k_per_group])
+    _check(_lib.pg_select_final(ctx, mode, k, draw, _stream(stream)))
+
+
 def pg_policy_ratio(ctx, weights_new, clip_eps, logp_new, ratio, J, stream=None):
     _check(_lib.pg_policy_ratio(ctx, _ptr(weights_new), clip_eps, _ptr(logp_new), _ptr(ratio), _ptr(J), _stream(stream)))
 
@@ -346,6 +357,16 @@ def pg_ovf_scratch_ints(n_groups):
 def pg_ovf_select(rewards, group_offsets, k, n_groups, masks, sel_idx, new_offsets, status, scratch, stream=None):
     _check(_lib.pg_ovf_select(_ptr(rewards), _ptr(group_offsets), _ptr(k), n_groups, _ptr(masks), _ptr(sel_idx),
                               _ptr(new_offsets), _ptr(status), _ptr(scratch), _stream(stream)))
+
+
+def pg_uniform_select(group_offsets, k, n_groups, seed, draw, masks, sel_idx, new_offsets, status, scratch, stream=None):
+    _check(_lib.pg_uniform_select(_ptr(group_offsets), _ptr(k), n_groups, seed, draw, _ptr(masks), _ptr(sel_idx),
+                                  _ptr(new_offsets), _ptr(status), _ptr(scratch), _stream(stream)))
+
+
+def pg_group_stats(rewards, group_offsets, n_groups, delta, sigma, clustered_share, stream=None):
+    _check(_lib.pg_group_stats(_ptr(rewards), _ptr(group_offsets), n_groups, delta, _ptr(sigma), _ptr(clustered_share),
+                               _stream(stream)))
 
 
 def pg_compact_gather(x, out, src, n_out, d, stream=None):

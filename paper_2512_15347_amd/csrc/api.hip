@@ -347,7 +347,7 @@ extern "C" pg_status pg_bind(pg_ctx* c, const pg_buffers* b) {
       ((uintptr_t)b->ctx & 15))
     return fail(PG_ESHAPE, "pg_bind: buffers must be 16-byte aligned (workspace 256)");
   if (!c->staging) {
-    const size_t n = (size_t)(c->cfg.T + 1) * (2 * c->cfg.P + 2);
+    const size_t n = (size_t)(c->cfg.T + 2) * (2 * c->cfg.P + 2);   // one slot per step, one for init, one for the final selection
     PG_HIP(hipHostMalloc((void**)&c->staging, n * sizeof(int32_t), hipHostMallocDefault));
   }
   c->buf = *b;
@@ -516,6 +516,52 @@ extern "C" pg_status pg_advantages(pg_ctx* c, void* stream) {
                            c->cfg.probe_bias, (float*)ws(c, c->ws_partials), stream));
   PG_TRY(pg_group_advantages(c->buf.rewards, c->buf.group_offsets, c->cfg.P, c->cfg.adv_eps, c->buf.adv, stream));
   c->advantages_done = true;
+  return PG_OK;
+}
+
+// Comparison arms of Sec. 4.1-4.2 on a finished run: select on the FINAL rewards (mode 0: Optimal Variance
+// Filtering applied once after sampling, mode 1: a uniformly random k-subset), pack the kept trajectories
+// and recompute Eq. 18 on them.
+extern "C" pg_status pg_select_final(pg_ctx* c, int32_t mode, const int32_t* k_per_group, uint32_t draw, void* stream) {
+  if (!c || !c->bound || !c->initialised) return fail(PG_ESCHED, "pg_select_final: call pg_init_group first");
+  if (!c->advantages_done) return fail(PG_ESCHED, "pg_select_final: call pg_advantages first (final rewards)");
+  if (mode != 0 && mode != 1) return fail(PG_EINVAL, "pg_select_final: mode %d (0: OVF, 1: uniform)", mode);
+  if (!k_per_group) return fail(PG_EINVAL, "pg_select_final: k_per_group is NULL");
+  hipStream_t s = (hipStream_t)stream;
+  const int P = c->cfg.P;
+  std::vector<int> new_off(P + 1, 0);
+  for (int g = 0; g < P; ++g) {
+    const int n = c->offsets[g + 1] - c->offsets[g];
+    if (k_per_group[g] < 1 || k_per_group[g] > n)
+      return fail(PG_EINVAL, "pg_select_final: k = %d for group %d of %d trajectories", k_per_group[g], g, n);
+    new_off[g + 1] = new_off[g] + k_per_group[g];
+  }
+  int32_t* slot = c->staging + (size_t)(c->cfg.T + 1) * (2 * P + 2);
+  memcpy(slot, k_per_group, sizeof(int32_t) * P);
+  memcpy(slot + P, new_off.data(), sizeof(int32_t) * (P + 1));
+  PG_HIP(hipMemcpyAsync(ws(c, c->ws_k), slot, sizeof(int32_t) * P, hipMemcpyHostToDevice, s));
+  PG_HIP(hipMemcpyAsync(ws(c, c->ws_newoff), slot + P, sizeof(int32_t) * (P + 1), hipMemcpyHostToDevice, s));
+  if (mode == 0)
+    PG_TRY(launch_ovf(c->buf.rewards, c->buf.group_offsets, (int32_t*)ws(c, c->ws_k), P,
+                      (int32_t*)ws(c, c->ws_newoff), c->buf.masks, c->buf.sel_idx, c->buf.status, s));
+  else
+    PG_TRY(launch_uniform_select(c->buf.group_offsets, (int32_t*)ws(c, c->ws_k), P, (int32_t*)ws(c, c->ws_newoff),
+                                 c->seed, draw, c->buf.masks, c->buf.sel_idx, c->buf.status, s));
+  const int M_new = new_off[P];
+  PG_TRY(pg_compact_gather(c->buf.x[c->cur_x], c->buf.x[1 - c->cur_x], c->buf.sel_idx, M_new, c->d, stream));
+  c->cur_x = 1 - c->cur_x;
+  // rewards are gathered as 32-bit patterns through scratch
+  int32_t* tmp = (int32_t*)ws(c, c->ws_partials);
+  PG_TRY(launch_gather_ids((const int32_t*)c->buf.rewards, c->buf.sel_idx, M_new, tmp, s));
+  PG_HIP(hipMemcpyAsync(c->buf.rewards, tmp, sizeof(float) * M_new, hipMemcpyDeviceToDevice, s));
+  PG_TRY(launch_gather_ids(c->buf.orig_id[c->cur_id], c->buf.sel_idx, M_new, c->buf.orig_id[1 - c->cur_id], s));
+  c->cur_id = 1 - c->cur_id;
+  PG_HIP(hipMemcpyAsync(c->buf.group_offsets, ws(c, c->ws_newoff), sizeof(int32_t) * (P + 1),
+                        hipMemcpyDeviceToDevice, s));
+  PG_TRY(launch_fill_group_of(c->buf.group_offsets, P, c->buf.group_of, s));
+  c->offsets = new_off;
+  c->M = M_new;
+  PG_TRY(pg_group_advantages(c->buf.rewards, c->buf.group_offsets, P, c->cfg.adv_eps, c->buf.adv, stream));
   return PG_OK;
 }
 

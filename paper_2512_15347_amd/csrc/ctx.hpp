@@ -62,6 +62,9 @@ pg_status launch_gather_ids(const int32_t* in, const int32_t* sel, int n_out, in
 pg_status launch_fill_group_of(const int32_t* offsets, int n_groups, int32_t* group_of, hipStream_t s);
 pg_status launch_masks_to_sel(const uint64_t* masks, const int32_t* offsets, const int32_t* new_offsets,
                               int n_groups, int32_t* sel_idx, hipStream_t s);
+pg_status launch_uniform_select(const int32_t* offsets, const int32_t* k, int n_groups, const int32_t* new_offsets,
+                                uint64_t seed, uint32_t draw, uint64_t* masks, int32_t* sel_idx, int32_t* status,
+                                hipStream_t s);
 pg_status launch_ovf(const float* rewards, const int32_t* offsets, const int32_t* k, int n_groups,
                      const int32_t* new_offsets, uint64_t* masks, int32_t* sel_idx, int32_t* status,
                      hipStream_t s);

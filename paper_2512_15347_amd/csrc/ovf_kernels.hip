@@ -7,6 +7,7 @@
 // for the survivor mask.  Why k+1 candidates are enough: with the other members fixed the variance
 // is a convex quadratic in one member's value, so some optimum is "j lowest and k-j highest".
 #include "common.hpp"
+#include "philox.hpp"
 
 namespace pg {
 
@@ -168,6 +169,70 @@ __global__ __launch_bounds__(OVF_WAVES * WAVE) void group_advantages_kernel(
   for (int i = b + lane; i < e; i += WAVE) adv[i] = (float)(((double)rewards[i] - mu) / (sigma + eps));
 }
 
+// ---- comparison arm of Sec. 4.1: a uniformly random k-subset per group ----
+// Slot j of group g draws one 32-bit key, word 0 of the Philox-4x32-10 block with counter
+// (j, draw, g, STREAM_SUBSAMPLE) under the run's seed; the k slots with the smallest (key, slot) stay.
+constexpr uint32_t STREAM_SUBSAMPLE = 2u;
+
+__global__ __launch_bounds__(OVF_WAVES * WAVE) void uniform_select_kernel(
+    const int32_t* __restrict__ offsets, const int32_t* __restrict__ kk, int n_groups,
+    const int32_t* __restrict__ new_offsets, uint32_t k0, uint32_t k1, uint32_t draw,
+    uint64_t* __restrict__ masks, int32_t* __restrict__ sel_idx, int32_t* __restrict__ status) {
+  const int wv = threadIdx.x / WAVE, lane = threadIdx.x & (WAVE - 1);
+  const int g = blockIdx.x * OVF_WAVES + wv;
+  if (g >= n_groups) return;
+  const int b = offsets[g];
+  const int n = offsets[g + 1] - b;
+  const int k = kk[g];
+  const int out0 = new_offsets[g];
+  if (n < 1 || n > WAVE || k < 1 || k > n) {
+    if (lane == 0) {
+      if (!(n == 0 && k == 0)) atomicOr(status, 2);
+      masks[g] = 0ull;
+    }
+    return;
+  }
+  const uint32_t key = philox4x32_10(u32x4{(uint32_t)lane, draw, (uint32_t)g, STREAM_SUBSAMPLE}, k0, k1).x;
+  int rank = 0;
+  for (int l = 0; l < n; ++l) {
+    const uint32_t kl = (uint32_t)__shfl((int)key, l, WAVE);
+    rank += (kl < key || (kl == key && l < lane)) ? 1 : 0;
+  }
+  const bool keep = lane < n && rank < k;
+  const uint64_t mask = __ballot(keep);
+  if (keep) sel_idx[out0 + __popcll(mask & ((1ull << lane) - 1ull))] = b + lane;
+  if (lane == 0) masks[g] = mask;
+}
+
+// ---- group diagnostics: sigma_G (population) and the share of members within delta sigma_G of the
+// group mean (the clustered region of Eq. 7); one wave per group, any group size ----
+__global__ __launch_bounds__(OVF_WAVES * WAVE) void group_stats_kernel(
+    const float* __restrict__ rewards, const int32_t* __restrict__ offsets, int n_groups, double delta,
+    float* __restrict__ sigma_out, float* __restrict__ share_out) {
+  const int wv = threadIdx.x / WAVE, lane = threadIdx.x & (WAVE - 1);
+  const int g = blockIdx.x * OVF_WAVES + wv;
+  if (g >= n_groups) return;
+  const int b = offsets[g], e = offsets[g + 1];
+  const int n = e - b;
+  if (n <= 0) {
+    if (lane == 0) { if (sigma_out) sigma_out[g] = 0.f; if (share_out) share_out[g] = 0.f; }
+    return;
+  }
+  double s = 0.0;
+  for (int i = b + lane; i < e; i += WAVE) s += (double)rewards[i];
+  const double mu = wave_allsum_f64(s) / (double)n;
+  double q = 0.0;
+  for (int i = b + lane; i < e; i += WAVE) { const double dv = (double)rewards[i] - mu; q += dv * dv; }
+  const double sigma = sqrt(wave_allsum_f64(q) / (double)n);
+  int inside = 0;
+  for (int i = b + lane; i < e; i += WAVE) inside += (fabs((double)rewards[i] - mu) <= delta * sigma) ? 1 : 0;
+  for (int o = 32; o > 0; o >>= 1) inside += __shfl_xor(inside, o, WAVE);
+  if (lane == 0) {
+    if (sigma_out) sigma_out[g] = (float)sigma;
+    if (share_out) share_out[g] = (float)((double)inside / (double)n);
+  }
+}
+
 // ---- index bookkeeping around a prune ----
 __global__ void gather_ids_kernel(const int32_t* __restrict__ ids_in, const int32_t* __restrict__ sel,
                                   int n_out, int32_t* __restrict__ ids_out) {
@@ -239,6 +304,27 @@ pg_status launch_masks_to_sel(const uint64_t* masks, const int32_t* offsets, con
   return PG_OK;
 }
 
+pg_status launch_uniform_select(const int32_t* offsets, const int32_t* k, int n_groups, const int32_t* new_offsets,
+                                uint64_t seed, uint32_t draw, uint64_t* masks, int32_t* sel_idx, int32_t* status,
+                                hipStream_t s) {
+  uniform_select_kernel<<<dim3((n_groups + OVF_WAVES - 1) / OVF_WAVES), dim3(OVF_WAVES * WAVE), 0, s>>>(
+      offsets, k, n_groups, new_offsets, (uint32_t)seed, (uint32_t)(seed >> 32), draw, masks, sel_idx, status);
+  PG_LAUNCH_CHECK("uniform_select_kernel");
+  return PG_OK;
+}
+
+// exclusive scan of k into new_offsets (three launches), shared by the selection entry points
+static pg_status scan_k(const int32_t* k, int n_groups, int32_t* scratch, int32_t* new_offsets, hipStream_t s) {
+  const int n_blocks = (n_groups + SCAN_BLOCK - 1) / SCAN_BLOCK;
+  scan_block_sums_kernel<<<dim3(n_blocks), dim3(SCAN_THREADS), 0, s>>>(k, n_groups, scratch);
+  PG_LAUNCH_CHECK("scan_block_sums_kernel");
+  scan_sums_kernel<<<dim3(1), dim3(64), 0, s>>>(scratch, n_blocks);
+  PG_LAUNCH_CHECK("scan_sums_kernel");
+  scan_write_kernel<<<dim3(n_blocks), dim3(SCAN_THREADS), 0, s>>>(k, n_groups, scratch, new_offsets);
+  PG_LAUNCH_CHECK("scan_write_kernel");
+  return PG_OK;
+}
+
 // OVF with new_offsets already known (the sampling loop knows them from its schedule)
 pg_status launch_ovf(const float* rewards, const int32_t* offsets, const int32_t* k, int n_groups,
                      const int32_t* new_offsets, uint64_t* masks, int32_t* sel_idx, int32_t* status,
@@ -266,13 +352,7 @@ extern "C" pg_status pg_ovf_select(const float* rewards, const int32_t* group_of
   if (!rewards || !group_offsets || !k || !masks || !sel_idx || !new_offsets || !status || !scratch)
     return fail(PG_EINVAL, "pg_ovf_select: null pointer");
   hipStream_t s = (hipStream_t)stream;
-  const int n_blocks = (n_groups + SCAN_BLOCK - 1) / SCAN_BLOCK;
-  scan_block_sums_kernel<<<dim3(n_blocks), dim3(SCAN_THREADS), 0, s>>>(k, n_groups, scratch);
-  PG_LAUNCH_CHECK("scan_block_sums_kernel");
-  scan_sums_kernel<<<dim3(1), dim3(64), 0, s>>>(scratch, n_blocks);
-  PG_LAUNCH_CHECK("scan_sums_kernel");
-  scan_write_kernel<<<dim3(n_blocks), dim3(SCAN_THREADS), 0, s>>>(k, n_groups, scratch, new_offsets);
-  PG_LAUNCH_CHECK("scan_write_kernel");
+  PG_TRY(scan_k(k, n_groups, scratch, new_offsets, s));
   return launch_ovf(rewards, group_offsets, k, n_groups, new_offsets, masks, sel_idx, status, s);
 }
 
@@ -285,5 +365,29 @@ extern "C" pg_status pg_group_advantages(const float* rewards, const int32_t* gr
   group_advantages_kernel<<<dim3((n_groups + OVF_WAVES - 1) / OVF_WAVES), dim3(OVF_WAVES * WAVE), 0,
                             (hipStream_t)stream>>>(rewards, group_offsets, n_groups, eps, adv);
   PG_LAUNCH_CHECK("group_advantages_kernel");
+  return PG_OK;
+}
+
+extern "C" pg_status pg_uniform_select(const int32_t* group_offsets, const int32_t* k, int32_t n_groups,
+                                       uint64_t seed, uint32_t draw, uint64_t* masks, int32_t* sel_idx,
+                                       int32_t* new_offsets, int32_t* status, int32_t* scratch, void* stream) {
+  if (n_groups < 0) return fail(PG_EINVAL, "pg_uniform_select: n_groups = %d", n_groups);
+  if (n_groups == 0) return PG_OK;
+  if (!group_offsets || !k || !masks || !sel_idx || !new_offsets || !status || !scratch)
+    return fail(PG_EINVAL, "pg_uniform_select: null pointer");
+  hipStream_t s = (hipStream_t)stream;
+  PG_TRY(scan_k(k, n_groups, scratch, new_offsets, s));
+  return launch_uniform_select(group_offsets, k, n_groups, new_offsets, seed, draw, masks, sel_idx, status, s);
+}
+
+extern "C" pg_status pg_group_stats(const float* rewards, const int32_t* group_offsets, int32_t n_groups,
+                                    double delta, float* sigma, float* clustered_share, void* stream) {
+  if (n_groups < 0) return fail(PG_EINVAL, "pg_group_stats: n_groups = %d", n_groups);
+  if (!(delta >= 0.0)) return fail(PG_EINVAL, "pg_group_stats: delta = %g", delta);
+  if (n_groups == 0) return PG_OK;
+  if (!rewards || !group_offsets || (!sigma && !clustered_share)) return fail(PG_EINVAL, "pg_group_stats: null pointer");
+  group_stats_kernel<<<dim3((n_groups + OVF_WAVES - 1) / OVF_WAVES), dim3(OVF_WAVES * WAVE), 0,
+                       (hipStream_t)stream>>>(rewards, group_offsets, n_groups, delta, sigma, clustered_share);
+  PG_LAUNCH_CHECK("group_stats_kernel");
   return PG_OK;
 }

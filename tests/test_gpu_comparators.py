@@ -1,0 +1,186 @@
+"""GPU parity of the comparison arms (uniform k-subset, static OVF on final rewards) and of the group
+diagnostics (sigma_G, clustered share of Eq. 7) through the C ABI, against oracle/comparators.py."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import comparators as cmp, loop, sampler
+from paper_2512_15347_amd import workloads
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def _ragged(rng, n_groups, lo=1, hi=64):
+    sizes = rng.integers(lo, hi + 1, n_groups)
+    offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    k = np.array([rng.integers(1, s + 1) for s in sizes], dtype=np.int32)
+    return sizes, offs, k
+
+
+@pytest.mark.parametrize("seed,draw,n_groups", [(7, 0, 37), (0xFEDCBA9876543210, 5, 4500)])
+def test_uniform_select_matches_oracle_bit_for_bit(lib, seed, draw, n_groups):
+    say(f"uniform_select seed {seed:#x} draw {draw} groups {n_groups}")
+    rng = np.random.default_rng(n_groups)
+    sizes, offs, k = _ragged(rng, n_groups)
+    k[0] = sizes[0]                                    # keep-all group
+    want_masks, want_sel, want_off = cmp.uniform_groups(seed, draw, offs, k)
+    t = lambda a, dt: torch.from_numpy(np.asarray(a).astype(dt)).to(DEV)
+    masks = torch.zeros(n_groups, dtype=torch.int64, device=DEV)
+    sel = torch.full((int(k.sum()),), -1, dtype=torch.int32, device=DEV)
+    noff = torch.zeros(n_groups + 1, dtype=torch.int32, device=DEV)
+    status = torch.zeros(4, dtype=torch.int32, device=DEV)
+    scratch = torch.zeros(lib.pg_ovf_scratch_ints(n_groups), dtype=torch.int32, device=DEV)
+    lib.pg_uniform_select(t(offs, np.int32), t(k, np.int32), n_groups, seed, draw, masks, sel, noff, status, scratch)
+    torch.cuda.synchronize()
+    assert status[0].item() == 0
+    np.testing.assert_array_equal(masks.cpu().numpy().view(np.uint64), want_masks)
+    np.testing.assert_array_equal(noff.cpu().numpy(), want_off)
+    np.testing.assert_array_equal(sel.cpu().numpy(), want_sel)
+
+
+def test_uniform_select_flags_bad_k_and_oversized_groups(lib):
+    offs = torch.tensor([0, 5, 5, 75, 80], dtype=torch.int32, device=DEV)        # sizes 5, 0, 70, 5
+    k = torch.tensor([6, 0, 3, 2], dtype=torch.int32, device=DEV)
+    masks = torch.full((4,), -1, dtype=torch.int64, device=DEV)
+    sel = torch.full((11,), -1, dtype=torch.int32, device=DEV)
+    noff = torch.zeros(5, dtype=torch.int32, device=DEV)
+    status = torch.zeros(4, dtype=torch.int32, device=DEV)
+    scratch = torch.zeros(lib.pg_ovf_scratch_ints(4), dtype=torch.int32, device=DEV)
+    lib.pg_uniform_select(offs, k, 4, 1, 0, masks, sel, noff, status, scratch)
+    torch.cuda.synchronize()
+    assert status[0].item() == 2
+    m = masks.cpu().numpy().view(np.uint64)
+    assert m[0] == 0 and m[1] == 0 and m[2] == 0 and bin(int(m[3])).count("1") == 2
+    want = cmp.uniform_subset(1, 0, 3, 5, 2)
+    assert int(m[3]) == want[0]
+    assert sel.cpu().numpy()[9:].tolist() == [75 + j for j in want[1]]
+
+
+def test_group_stats_matches_oracle(lib):
+    say("group_stats")
+    rng = np.random.default_rng(3)
+    sizes = np.array([1, 2, 17, 64, 0, 100, 24, 48, 33, 5])
+    offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    r = np.concatenate([workloads.stress_rewards(1, int(s), seed=11 + i)[0] if s else np.zeros(0, np.float32)
+                        for i, s in enumerate(sizes)]).astype(np.float32)
+    r[offs[5]:offs[6]] += 20.0                          # reward models score around 20
+    for delta in (0.5, 1.0):
+        want_sig, want_share = cmp.group_stats(r, offs, delta)
+        sig = torch.zeros(len(sizes), device=DEV); share = torch.zeros(len(sizes), device=DEV)
+        lib.pg_group_stats(torch.from_numpy(r).to(DEV), torch.from_numpy(offs).to(DEV), len(sizes), delta, sig, share)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(sig.cpu().numpy(), want_sig, rtol=2e-7, atol=0)
+        # membership is decided in fp64 on both sides; a member within rounding of the boundary may differ
+        rr = r.astype(np.float64)
+        for g in range(len(sizes)):
+            b, e = offs[g], offs[g + 1]
+            if e == b:
+                assert share[g].item() == 0.0
+                continue
+            margin = np.abs(np.abs(rr[b:e] - rr[b:e].mean()) - delta * want_sig[g])
+            loose = np.count_nonzero(margin < 1e-9 * max(want_sig[g], 1e-30))
+            assert abs(share[g].item() * (e - b) - want_share[g] * (e - b)) <= loose + 1e-3, g
+    # hand example of the oracle pin: 0,0,0,0,10 -> sigma 4, share 0.8 at delta 0.5 (exact in fp64)
+    sig = torch.zeros(1, device=DEV); share = torch.zeros(1, device=DEV)
+    lib.pg_group_stats(torch.tensor([0., 0, 0, 0, 10], device=DEV), torch.tensor([0, 5], dtype=torch.int32, device=DEV),
+                       1, 0.5, sig, share)
+    torch.cuda.synchronize()
+    assert sig.item() == 4.0 and abs(share.item() - 0.8) < 1e-7
+
+
+def _run_injected(lib, cfg, seed):
+    """Library loop driven by the oracle's network output; returns (ctx, buf, oracle record)."""
+    w = workloads.make_weights(cfg)
+    inp = workloads.make_inputs(cfg, w)
+    s = cfg["sampler"]
+    tables = (sampler.flow_sde_tables(cfg["T"], s["a"]) if s["kind"] == "flow"
+              else sampler.ddim_sde_tables(cfg["T"], s["eta"], s["beta0"], s["beta1"], s["T_train"]))
+    rec = loop.run(cfg, tables, inp, seed, wts=w, keep_u_steps=range(cfg["T"]))
+    c, keep = lib.make_config(cfg, probe_bias=inp["probe_b"], net=False)
+    ctx = lib.pg_create(c)
+    buf = lib.Buffers(ctx, cfg, inputs=inp)
+    lib.pg_bind(ctx, buf)
+    lib.pg_init_group(ctx, seed)
+    for st in range(cfg["T"]):
+        ids_s, u_s = rec["u"][st]
+        M = lib.pg_state(ctx, cfg["P"])["M"]
+        assert M == len(ids_s)
+        buf.u[:M].copy_(torch.from_numpy(u_s.astype(np.float32)))
+        lib.pg_net_forward(ctx, st)
+        if st in rec["ovf_masks"]:
+            lib.pg_prune(ctx, st)
+        lib.pg_step(ctx, st)
+    lib.pg_advantages(ctx)
+    lib.pg_check(ctx)
+    return ctx, buf, rec
+
+
+@pytest.mark.parametrize("name,mode,kk", [("cfg1", 0, [4]), ("cfg1", 1, [3]), ("cfg4_small", 0, [2, 3, 5]),
+                                          ("cfg4_small", 1, [4, 1, 12])])
+def test_select_final_on_a_finished_run(lib, name, mode, kk):
+    """Static selection after sampling (Sec. 4.2) and the uniform arm: selection, packing and the advantages
+    of the kept members against the oracle applied to its own final rewards."""
+    say(f"select_final {name} mode {mode} k {kk}")
+    cfg = workloads.get_config(name)
+    if name == "cfg1":
+        cfg["schedule"] = [[]]                          # no in-loop pruning: the full group reaches the end
+    seed, draw = 2512, 9
+    ctx, buf, rec = _run_injected(lib, cfg, seed)
+    P = cfg["P"]
+    st = lib.pg_state(ctx, P)
+    x_before = buf.x[st["cur_x"]][:st["M"]].clone()
+    ids_before = buf.orig_id[st["cur_id"]][:st["M"]].clone()
+    rew_before = buf.rewards[:st["M"]].clone()
+    want = cmp.select_final(rec["rewards"], rec["offsets"], kk, mode, seed=seed, draw=draw, eps=1e-6)
+    lib.pg_select_final(ctx, mode, kk, draw)
+    lib.pg_check(ctx)
+    st2 = lib.pg_state(ctx, P)
+    Mn = st2["M"]
+    assert Mn == int(want["offsets"][-1]) and st2["offsets"] == want["offsets"].tolist()
+    np.testing.assert_array_equal(buf.masks.cpu().numpy().view(np.uint64)[:P], want["masks"])
+    sel = buf.sel_idx.cpu().numpy()[:Mn]
+    np.testing.assert_array_equal(sel, want["sel_idx"])
+    np.testing.assert_array_equal(buf.group_offsets.cpu().numpy(), want["offsets"])
+    # packing is a bitwise copy of the kept rows
+    idx = torch.from_numpy(sel.astype(np.int64)).to(DEV)
+    assert torch.equal(buf.x[st2["cur_x"]][:Mn], x_before[idx])
+    assert torch.equal(buf.orig_id[st2["cur_id"]][:Mn], ids_before[idx])
+    assert torch.equal(buf.rewards[:Mn], rew_before[idx])
+    np.testing.assert_array_equal(buf.orig_id[st2["cur_id"]][:Mn].cpu().numpy(), rec["orig_id"][want["sel_idx"]])
+    gof = buf.group_of.cpu().numpy()[:Mn]
+    for g in range(P):
+        assert np.all(gof[want["offsets"][g]:want["offsets"][g + 1]] == g)
+    adv = buf.adv.cpu().numpy()[:Mn].astype(np.float64)
+    for g in range(P):
+        b, e = want["offsets"][g], want["offsets"][g + 1]
+        if e - b > 1:
+            np.testing.assert_allclose(adv[b:e], want["adv"][b:e], rtol=2e-3, atol=2e-3)
+    # sigma_G of the kept members: the OVF arm never falls below the full group (Sec. 4.2)
+    sig_before, _ = cmp.group_stats(rec["rewards"], rec["offsets"], 1.0)
+    sig = torch.zeros(P, device=DEV)
+    lib.pg_group_stats(buf.rewards, buf.group_offsets, P, 1.0, sig, None)
+    torch.cuda.synchronize()
+    sig_after, _ = cmp.group_stats(want["rewards"], want["offsets"], 1.0)
+    np.testing.assert_allclose(sig.cpu().numpy(), sig_after, rtol=1e-3, atol=1e-6)
+    if mode == 0:
+        assert np.all(sig.cpu().numpy() >= sig_before * (1 - 1e-3))
+    lib.pg_destroy(ctx)
+
+
+def test_select_final_argument_errors(lib):
+    cfg = workloads.get_config("cfg1")
+    w = workloads.make_weights(cfg); inp = workloads.make_inputs(cfg, w)
+    c, keep = lib.make_config(cfg, probe_bias=inp["probe_b"], net=False)
+    ctx = lib.pg_create(c)
+    buf = lib.Buffers(ctx, cfg, inputs=inp)
+    lib.pg_bind(ctx, buf)
+    lib.pg_init_group(ctx, 1)
+    with pytest.raises(lib.PgError):                    # no final rewards yet
+        lib.pg_select_final(ctx, 0, [2])
+    torch.cuda.synchronize()
+    lib.pg_destroy(ctx)
