@@ -7,6 +7,11 @@
 // exchange with the other half-wave.  The probabilities then feed O^T = V^T P^T directly from the
 // accumulator registers; the key order inside each 16-key contraction is permuted the same way in the
 // V^T operand read from LDS, which is why V is stored transposed ([head dim][key]) by the QKV GEMM.
+// The softmax's VALU work, not the MFMAs, sets the pace here, so it is kept minimal: the queries arrive
+// pre-multiplied by log2(e)/sqrt(hd) (by the projection GEMM's epilogue), the score accumulators start
+// at minus the running reference exponent, so a probability is a bare exp2 of the accumulator, and the
+// masking of keys past the end exists only in the code for the last, partial tile.
+#include <type_traits>
 #include "attention.hpp"
 
 namespace pg {
@@ -43,8 +48,15 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(const AttnArg
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
-  const int b = blockIdx.z, h = blockIdx.y;
-  const int q0 = blockIdx.x * QTILE + wave * 32;
+  // Workgroups are dealt to the 8 XCDs round-robin by id; the ids are permuted so that each XCD gets a
+  // contiguous run of (batch, head, query tile): the query tiles of one head then share its keys and
+  // values through one L2 instead of fetching them once per XCD.
+  const int nq = (a.Lq + QTILE - 1) / QTILE;
+  const int per_xcd = gridDim.x / 8;
+  const int wg = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (wg >= nq * a.heads * a.B) return;
+  const int b = wg / (nq * a.heads), h = (wg / nq) % a.heads;
+  const int q0 = (wg % nq) * QTILE + wave * 32;
   const int kb = a.kv_map ? a.kv_map[b] : b;
   const uint16_t* kbase = a.k + (int64_t)kb * a.k_bstride + h * HD;
   const uint16_t* vbase = a.vt + (int64_t)kb * a.vt_bstride + (int64_t)h * HD * a.Lkpad;
@@ -56,6 +68,12 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(const AttnArg
     const uint16_t* qp = a.q + ((int64_t)b * a.Lq + qr) * a.ldq + h * HD + 8 * half;
 #pragma unroll
     for (int s = 0; s < SLABS; ++s) qf[s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
+    if (!a.q_prescaled) {
+#pragma unroll
+      for (int s = 0; s < SLABS; ++s)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[s][e] = (__bf16)((float)qf[s][e] * a.scale_log2);
+    }
   }
 
   f32x16 o[OT];
@@ -64,11 +82,11 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(const AttnArg
 #pragma unroll
     for (int e = 0; e < 16; ++e) o[t][e] = 0.f;
   // Running softmax statistics in the log2 domain.  m_run is a reference exponent, not necessarily the
-  // exact running maximum: it is only raised (and the accumulators rescaled) when a new score exceeds
-  // it by more than 2^8, so most tiles skip the rescale; probabilities stay below 2^8, well inside
-  // bf16 / fp32 range, and the final division by l makes the result independent of the reference.
-  float m_run = -__builtin_huge_valf(), l_run = 0.f;
-  const float c = a.scale_log2;
+  // exact running maximum: after the first tile it is only raised (and the accumulators rescaled) when a
+  // new score exceeds it by more than 2^8, so most tiles skip the rescale; probabilities stay below 2^8,
+  // well inside bf16 / fp32 range, and the final division by l makes the result independent of the
+  // reference.
+  float m_run = 0.f, l_run = 0.f;
 
   const int n_tiles = (a.Lk + KTILE - 1) / KTILE;
   u32x4v rk[K_PER_THREAD], rv[V_PER_THREAD];
@@ -124,59 +142,64 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(const AttnArg
     for (int i = 0; i < V_PER_THREAD; ++i) *reinterpret_cast<u32x4v*>(sV + v_off(v_row[i], v_ch[i])) = rv[i];
   };
 
-  load_tile(0);
-  for (int kt = 0; kt < n_tiles; ++kt) {
+  // one key tile; MASKED is the variant for a last tile that holds keys past the end
+  auto tile = [&](int kt, auto masked_c) {
+    constexpr bool MASKED = decltype(masked_c)::value;
     __syncthreads();                             // everyone is done reading the previous tile
     store_tile();
     __syncthreads();
     if (kt + 1 < n_tiles) load_tile(kt + 1);     // overlaps with the math below
 
-    // ---- S^T = K Q^T : two 32-key tiles ----
+    // ---- S^T = K Q^T - m_run : two 32-key tiles ----
+    const float neg_m = -m_run;
     f32x16 s[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) s[t][e] = 0.f;
+      for (int e = 0; e < 16; ++e) s[t][e] = neg_m;
 #pragma unroll
       for (int ks = 0; ks < SLABS; ++ks) {
         const bf16x8 kf = *reinterpret_cast<const bf16x8*>(sK + k_off<HD>(t * 32 + l32, 2 * ks + half));
         s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[t], 0, 0, 0);
       }
     }
-    // ---- online softmax for this lane's query ----
-    const int k0 = kt * KTILE;
-    if (k0 + KTILE > a.Lk) {                     // only the last tile can hold keys past the end
+    if (MASKED) {
+      const int k0 = kt * KTILE;
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int e = 0; e < 16; ++e)
           if (k0 + t * 32 + 8 * (e >> 2) + 4 * half + (e & 3) >= a.Lk) s[t][e] = -__builtin_huge_valf();
     }
+    // ---- online softmax for this lane's query; scores are already relative to m_run ----
     float mx = s[0][0];
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[t][e]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE)) * c;
-    if (__builtin_amdgcn_ballot_w64(mx > m_run + 8.0f) != 0ull) {     // wave-uniform: rare after the first tile
-      const float m_new = fmaxf(m_run, mx);
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      m_run = m_new;
+    mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+    if (kt == 0 || __builtin_amdgcn_ballot_w64(mx > 8.0f) != 0ull) {   // wave-uniform: rare after the first tile
+      const float delta = kt == 0 ? mx : fmaxf(mx, 0.f);               // the first tile sets the reference
+      const float alpha = __builtin_amdgcn_exp2f(-delta);
+      m_run += delta;
       l_run *= alpha;
 #pragma unroll
       for (int t = 0; t < OT; ++t)
 #pragma unroll
         for (int e = 0; e < 16; ++e) o[t][e] *= alpha;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s[t][e] -= delta;
     }
-    const float neg_m = -m_run;
     float psum = 0.f;
     bf16x8 pf[2][2];
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int e = 0; e < 16; e += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[t][e], c, neg_m));
-        const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[t][e + 1], c, neg_m));
+        const float p0 = __builtin_amdgcn_exp2f(s[t][e]);
+        const float p1 = __builtin_amdgcn_exp2f(s[t][e + 1]);
         const f32x2v pp = {p0, p1};
         const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
         // the normaliser sums the probabilities as the value product sees them (rounded to bf16)
@@ -201,7 +224,12 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(const AttnArg
           o[ot] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t][jj], o[ot], 0, 0, 0);
         }
       }
-  }
+  };
+
+  load_tile(0);
+  const int n_full = a.Lk / KTILE;               // tiles that lie wholly inside the keys
+  for (int kt = 0; kt < n_full; ++kt) tile(kt, std::false_type{});
+  if (n_full < n_tiles) tile(n_full, std::true_type{});
 
   // ---- normalise and store: lane holds head-dim rows 8*(e/4) + 4*half + e%4 of its query ----
   const float l_tot = l_run + __shfl_xor(l_run, 32, WAVE);
@@ -228,8 +256,9 @@ pg_status launch_attention(const AttnArgs& a, int hd, hipStream_t s) {
   if (a.Lkpad % 8 || a.Lkpad < a.Lk || a.ldq % 8 || a.ldk % 8 || a.ldo % 4 ||
       ((uintptr_t)a.q & 15) || ((uintptr_t)a.k & 15) || ((uintptr_t)a.vt & 15) || ((uintptr_t)a.out & 7))
     return fail(PG_ESHAPE, "attention: operands need 16-byte aligned rows");
-  if (a.heads > 65535 || a.B > 65535) return fail(PG_ESHAPE, "attention: grid limit");
-  const dim3 grid((a.Lq + QTILE - 1) / QTILE, a.heads, a.B);
+  const int64_t wgs = (int64_t)((a.Lq + QTILE - 1) / QTILE) * a.heads * a.B;
+  if (wgs > (1ll << 30)) return fail(PG_ESHAPE, "attention: grid limit");
+  const dim3 grid((unsigned)((wgs + 7) / 8 * 8));
   const int rec = prof_open(PROF_ATTENTION, 4.0 * a.B * (double)a.heads * a.Lq * (double)a.Lk * hd, s);
   if (hd == 64) attention_kernel<64><<<grid, dim3(ATT_THREADS), 0, s>>>(a);
   else attention_kernel<32><<<grid, dim3(ATT_THREADS), 0, s>>>(a);

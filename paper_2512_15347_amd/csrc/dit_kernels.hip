@@ -334,11 +334,12 @@ pg_status net_forward(pg_ctx* c, int step, const float* x_in, const uint16_t* we
       GemmArgs g{};
       g.A = act; g.lda = D; g.W = n.w(PG_W_QKV_W, b); g.ldw = n.ld(PG_W_QKV_W); g.bias = n.w(PG_W_QKV_B, b);
       g.M = R; g.N = 3 * D; g.K = D; g.outb = qk; g.ldob = 2 * D; g.vt = vt; g.v_start = 2 * D; g.Lpad = Lpad; g.L = L;
+      g.out_scale = scale_log2; g.scale_cols = D;   // queries leave the projection already in the softmax's log2 units
       PG_TRY(launch_gemm(g, EPI_QKV, s));
       AttnArgs a{};
       a.q = qk; a.ldq = 2 * D; a.k = qk + D; a.ldk = 2 * D; a.k_bstride = (int64_t)L * 2 * D;
       a.vt = vt; a.vt_bstride = (int64_t)D * Lpad; a.Lkpad = Lpad; a.out = att; a.ldo = D;
-      a.B = M; a.Lq = L; a.Lk = L; a.heads = f.heads; a.scale_log2 = scale_log2;
+      a.B = M; a.Lq = L; a.Lk = L; a.heads = f.heads; a.scale_log2 = scale_log2; a.q_prescaled = 1;
       PG_TRY(launch_attention(a, hd, s));
       GemmArgs o{};
       o.A = att; o.lda = D; o.W = n.w(PG_W_O_W, b); o.ldw = n.ld(PG_W_O_W); o.bias = n.w(PG_W_O_B, b);
@@ -352,13 +353,14 @@ pg_status net_forward(pg_ctx* c, int step, const float* x_in, const uint16_t* we
       GemmArgs g{};
       g.A = act; g.lda = D; g.W = n.w(PG_W_CQ_W, b); g.ldw = n.ld(PG_W_CQ_W); g.bias = n.w(PG_W_CQ_B, b);
       g.M = R; g.N = D; g.K = D; g.outb = qk; g.ldob = D;
+      g.out_scale = scale_log2; g.scale_cols = D;
       PG_TRY(launch_gemm(g, EPI_BF16, s));
       AttnArgs a{};
       a.q = qk; a.ldq = D;
       a.k = n.at<uint16_t>(pl.ckv) + (size_t)b * P * f.Lc * D; a.ldk = D; a.k_bstride = (int64_t)f.Lc * D;
       a.vt = n.at<uint16_t>(pl.ckvt) + (size_t)b * P * D * Lcpad; a.vt_bstride = (int64_t)D * Lcpad; a.Lkpad = Lcpad;
       a.out = att; a.ldo = D; a.kv_map = group_of;
-      a.B = M; a.Lq = L; a.Lk = f.Lc; a.heads = f.heads; a.scale_log2 = scale_log2;
+      a.B = M; a.Lq = L; a.Lk = f.Lc; a.heads = f.heads; a.scale_log2 = scale_log2; a.q_prescaled = 1;
       PG_TRY(launch_attention(a, hd, s));
       GemmArgs o{};
       o.A = att; o.lda = D; o.W = n.w(PG_W_CO_W, b); o.ldw = n.ld(PG_W_CO_W); o.bias = n.w(PG_W_CO_B, b);

@@ -373,6 +373,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
       return;
     }
     const bool n_ok = n < NN;                        // N is a multiple of 4
+    const float col_scale = n < a.scale_cols ? a.out_scale : 1.f;   // e.g. queries pre-multiplied by the softmax scale
     float4 b4 = {0.f, 0.f, 0.f, 0.f};
     if (PB && n_ok) {
       const uint2 raw = *reinterpret_cast<const uint2*>(PB + n);
@@ -394,6 +395,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
       for (int p = 0; p < NP; ++p) {
         v[p] = *reinterpret_cast<const float4*>(stg + (RPI * p + rsub) * EST + c4);
         v[p].x += b4.x; v[p].y += b4.y; v[p].z += b4.z; v[p].w += b4.w;
+        if (EPI == EPI_BF16 || EPI == EPI_QKV) { v[p].x *= col_scale; v[p].y *= col_scale; v[p].z *= col_scale; v[p].w *= col_scale; }
       }
       if (EPI == EPI_RESID) {
         // gates are per (group, column); a slab of 32 rows touches at most two trajectories when a
