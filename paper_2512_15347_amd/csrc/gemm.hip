@@ -513,11 +513,15 @@ static pg_status launch_tile(const GemmArgs& a, hipStream_t s) {
 // round is usually part empty, and with few K steps a tile's fixed prologue / epilogue weighs more.
 // Pick the shape with the best product of slot occupancy and the measured relative speed of its main
 // loop.  PROGRPO_GEMM_TILE (0..3) overrides the heuristic; it is a tuning aid.
-static int pick_tile(const GemmArgs& a) {
+static int pick_tile(const GemmArgs& a, int epilogue) {
   static const int forced = [] { const char* e = getenv("PROGRPO_GEMM_TILE"); return e ? atoi(e) : -1; }();
   if (forced >= 0 && forced <= 5) return forced;
+  // columns written row-major / produced through swapped operand roles (their tiles are BM channels x BN rows)
+  const int n_rm = epilogue == EPI_VT ? 0 : epilogue == EPI_QKV ? a.v_start : a.N;
+  const int n_sw = a.N - n_rm;
   auto score = [&](int bm, int bn, int per_cu, double speed) {
-    const double tiles = (double)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn);
+    const double tiles = (double)((a.M + bm - 1) / bm) * ((n_rm + bn - 1) / bn) +
+                         (double)((n_sw + bm - 1) / bm) * ((a.M + bn - 1) / bn);
     const double slots = 256.0 * per_cu;
     const double useful = (double)a.M * a.N / ((double)bm * bn);      // ragged edge tiles do less work
     return speed * useful / (ceil(tiles / slots) * slots);
@@ -533,7 +537,7 @@ template <int EPI>
 static pg_status launch_one(const GemmArgs& a, hipStream_t s) {
   static const bool dma = [] { const char* e = getenv("PROGRPO_GEMM_STAGING"); return !(e && e[0] == 'r'); }();
   if (dma) {
-    switch (pick_tile(a)) {
+    switch (pick_tile(a, EPI)) {
       case 0: return launch_tile<EPI, 256, 256, 64, 2, 4, 2, 2>(a, s);
       case 1: return launch_tile<EPI, 192, 256, 64, 2, 4, 2, 2>(a, s);
       case 2: return launch_tile<EPI, 128, 256, 64, 2, 4, 2, 2>(a, s);
@@ -542,7 +546,7 @@ static pg_status launch_one(const GemmArgs& a, hipStream_t s) {
       default: return launch_tile<EPI, 224, 256, 64, 1, 8, 2, 2>(a, s);    // one wave row, 32 columns per wave
     }
   }
-  switch (pick_tile(a)) {      // PROGRPO_GEMM_STAGING=regs: staging through registers (tuning aid)
+  switch (pick_tile(a, EPI)) {      // PROGRPO_GEMM_STAGING=regs: staging through registers (tuning aid)
     case 0: return launch_tile<EPI, 256, 256, 64, 2, 4, 2, 0>(a, s);
     case 1: return launch_tile<EPI, 192, 256, 64, 2, 4, 2, 0>(a, s);
     case 2: return launch_tile<EPI, 128, 256, 64, 2, 4, 2, 0>(a, s);

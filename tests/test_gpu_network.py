@@ -20,7 +20,11 @@ def bf16_dev(a):
     return torch.from_numpy(workloads.bf16_bits(a).view(np.int16)).to(DEV)
 
 
-@pytest.mark.parametrize("M,N,K", [(300, 200, 128), (2356, 384, 512), (256, 256, 64), (1, 16, 64), (777, 4608, 1536)])
+# the later shapes are sized so that the launcher's tile heuristic takes each of its tile heights (160, 192, 224,
+# 256 rows, and the 128x128 tile) with a ragged last tile in both directions
+@pytest.mark.parametrize("M,N,K", [(300, 200, 128), (2356, 384, 512), (256, 256, 64), (1, 16, 64), (777, 4608, 1536),
+                                   (12251, 768, 128), (12251, 2304, 64), (12283, 3072, 128), (24571, 1532, 64),
+                                   (18848, 1536, 64), (9001, 520, 192)])
 def test_gemm_matches_oracle_linear(lib, M, N, K):
     say(f"gemm M={M} N={N} K={K}")
     rng = np.random.default_rng(M + N + K)
