@@ -55,6 +55,11 @@ CONFIGS = {
     "cfg4_small": dict(P=3, N=12, C=4, H=16, W=16, T=6, sampler=_flow(), kind="joint",
                        D=128, blocks=2, heads=2, Lc=26, Dc=128,
                        schedule=[[(1, 8), (3, 4)], [(1, 7), (3, 5)], []]),
+    # dual-stream blocks with normalised queries / keys (the block structure of the flow model the paper trains)
+    "cfg3_mmdit_small": dict(P=2, N=6, C=4, H=16, W=16, T=4, sampler=_flow(), kind="mmdit",
+                             D=128, blocks=2, heads=2, Lc=26, Dc=128, schedule=[[(1, 3)], [(2, 4)]]),
+    "cfg3_mmdit": dict(P=1, N=48, C=16, H=64, W=64, T=10, sampler=_flow(), kind="mmdit",
+                       D=1536, blocks=24, heads=24, Lc=154, Dc=1536, schedule=[[(2, 32), (4, 16)]]),
     # the paper's own schedules (Sec. 6.1, experimental settings) on the small network
     "paper_std_small": dict(P=1, N=48, C=4, H=16, W=16, T=10, sampler=_flow(), kind="adaln",
                             D=128, blocks=2, heads=4, Lc=0, Dc=0, schedule=[[(5, 24), (7, 12)]]),
@@ -111,7 +116,7 @@ def weight_shapes(cfg):
     top = dict(pe_w=(D, 4 * C), pe_b=(D,), pos=(Li, D), t_w1=(D, 256), t_b1=(D,),
                t_w2=(D, D), t_b2=(D,), fmod_w=(2 * D, D), fmod_b=(2 * D,),
                f_w=(4 * C, D), f_b=(4 * C,))
-    if cfg["kind"] == "joint":
+    if cfg["kind"] in ("joint", "mmdit"):
         top.update(ctx_w=(D, Dc), ctx_b=(D,))
     blk = dict(mod_w=(6 * D, D), mod_b=(6 * D,), qkv_w=(3 * D, D), qkv_b=(3 * D,),
                o_w=(D, D), o_b=(D,), fc1_w=(4 * D, D), fc1_b=(4 * D,),
@@ -119,18 +124,23 @@ def weight_shapes(cfg):
     if cfg["kind"] == "cross":
         blk.update(cq_w=(D, D), cq_b=(D,), ckv_w=(2 * D, Dc), ckv_b=(2 * D,),
                    co_w=(D, D), co_b=(D,))
+    if cfg["kind"] == "mmdit":
+        hd = D // cfg["heads"]
+        blk.update({"c_" + k: v for k, v in list(blk.items())})          # the context stream's own copy
+        blk.update(qn_g=(hd,), kn_g=(hd,), c_qn_g=(hd,), c_kn_g=(hd,))    # per-channel scales of the query / key norms
     return top, blk
 
 
 def make_weights(cfg, seed=MASTER_SEED, std=0.02):
-    """All network tensors ~ N(0, std^2), rounded to bf16 once, returned as fp32."""
+    """All network tensors ~ N(0, std^2) (norm scales: 1 + N(0, std^2)), rounded to bf16 once, returned as fp32."""
     top, blk = weight_shapes(cfg)
     w = {}
     for i, (name, shape) in enumerate(sorted(top.items())):
         w[name] = _normal([seed, 1000, i], shape, std)
     w["blocks"] = []
     for b in range(cfg["blocks"]):
-        w["blocks"].append({name: _normal([seed, b, i], shape, std)
+        w["blocks"].append({name: (bf16_round(1.0 + _normal([seed, b, i], shape, std)) if name.endswith("_g")
+                                   else _normal([seed, b, i], shape, std))
                             for i, (name, shape) in enumerate(sorted(blk.items()))})
     return w
 

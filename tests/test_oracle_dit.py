@@ -112,6 +112,77 @@ def test_forward_all_variants_vs_torch_assembly():
         assert np.std(got) > 1e-3                      # a live output, not zeros
 
 
+def _torch_forward_mmdit(w, cfg, x, t_in, y, ctx):
+    """The dual-stream network assembled from torch library routines only."""
+    C, H, W, D, h = cfg["C"], cfg["H"], cfg["W"], cfg["D"], cfg["heads"]
+    M = x.shape[0]; Li = cfg["Li"]; hd = D // h
+    lin = lambda a, wn, bn, d=w: F.linear(a, T64(d[wn]), T64(d[bn]))
+    img = T64(x).reshape(M, C, H, W)
+    hx = lin(F.unfold(img, kernel_size=2, stride=2).transpose(1, 2), "pe_w", "pe_b") + T64(w["pos"])
+    hc = lin(T64(ctx), "ctx_w", "ctx_b").expand(M, -1, -1)
+    half = 128
+    f = torch.exp(-math.log(10000.0) * torch.arange(half, dtype=torch.float64) / half)
+    emb = torch.cat([torch.cos(t_in * f), torch.sin(t_in * f)])
+    sc = F.silu(lin(F.silu(lin(emb, "t_w1", "t_b1")), "t_w2", "t_b2") + T64(y))
+    heads = lambda a: a.reshape(M, a.shape[1], h, hd).transpose(1, 2)
+    for blk in w["blocks"]:
+        parts = []
+        for hs, pre in ((hx, ""), (hc, "c_")):
+            mod = lin(sc, pre + "mod_w", pre + "mod_b", blk).chunk(6)
+            a = F.layer_norm(hs, (D,), eps=1e-6) * (1 + mod[1]) + mod[0]
+            q, k, v = lin(a, pre + "qkv_w", pre + "qkv_b", blk).chunk(3, dim=-1)
+            q = F.rms_norm(heads(q), (hd,), T64(blk[pre + "qn_g"]), eps=1e-6)
+            k = F.rms_norm(heads(k), (hd,), T64(blk[pre + "kn_g"]), eps=1e-6)
+            parts.append((mod, q, k, heads(v)))
+        q = torch.cat([parts[0][1], parts[1][1]], 2); k = torch.cat([parts[0][2], parts[1][2]], 2)
+        v = torch.cat([parts[0][3], parts[1][3]], 2)
+        o = F.scaled_dot_product_attention(q, k, v).transpose(1, 2).reshape(M, -1, D)
+        new = []
+        for (hs, pre), (mod, _, _, _), a in zip(((hx, ""), (hc, "c_")), parts, (o[:, :Li], o[:, Li:])):
+            hs = hs + mod[2] * lin(a, pre + "o_w", pre + "o_b", blk)
+            m = F.layer_norm(hs, (D,), eps=1e-6) * (1 + mod[4]) + mod[3]
+            hs = hs + mod[5] * lin(F.gelu(lin(m, pre + "fc1_w", pre + "fc1_b", blk), approximate="tanh"),
+                                   pre + "fc2_w", pre + "fc2_b", blk)
+            new.append(hs)
+        hx, hc = new
+    shf, scf = lin(sc, "fmod_w", "fmod_b").chunk(2)
+    o = F.layer_norm(hx, (D,), eps=1e-6) * (1 + scf) + shf
+    return F.fold(lin(o, "f_w", "f_b").transpose(1, 2), (H, W), kernel_size=2, stride=2).reshape(M, -1).numpy()
+
+
+def test_rms_norm_vs_torch():
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((3, 5, 4, 32)); g = 1.0 + 0.1 * rng.standard_normal(32)
+    want = F.rms_norm(T64(x), (32,), T64(g), eps=1e-6).numpy()
+    np.testing.assert_allclose(dit.rms_norm(x, g), want, rtol=1e-12, atol=1e-14)
+    # unit scale: every row has mean square 1 (up to eps)
+    assert np.allclose(np.mean(dit.rms_norm(x, np.ones(32)) ** 2, axis=-1), 1.0, atol=1e-5)
+
+
+def test_dual_stream_forward_vs_torch_assembly_and_joint_special_case():
+    cfg = workloads.get_config("cfg3_mmdit_small")
+    w = workloads.make_weights(cfg); inp = workloads.make_inputs(cfg, w)
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((3, cfg["d"]))
+    got = dit.forward(w, cfg, x, 650.0, inp["y"][1], inp["ctx"][1])
+    want = _torch_forward_mmdit(w, cfg, x, 650.0, inp["y"][1], inp["ctx"][1])
+    np.testing.assert_allclose(got, want, rtol=1e-9, atol=1e-12)
+    assert np.std(got) > 1e-3
+    # the norm scales are live inputs
+    w2 = {**w, "blocks": [dict(b) for b in w["blocks"]]}
+    w2["blocks"][0]["c_kn_g"] = w2["blocks"][0]["c_kn_g"] * 1.5
+    assert np.max(np.abs(dit.forward(w2, cfg, x, 650.0, inp["y"][1], inp["ctx"][1]) - got)) > 1e-7
+    # special case that reduces to the single-stream network: both streams share one set of weights and the
+    # query / key norms are switched off
+    cj = workloads.get_config("cfg3_small")
+    wj = workloads.make_weights(cj); ij = workloads.make_inputs(cj, wj)
+    wm = {**wj, "blocks": [{**b, **{"c_" + k: v for k, v in b.items()}} for b in wj["blocks"]]}
+    cm = {**cj, "kind": "mmdit", "qk_norm": False}
+    xj = rng.standard_normal((2, cj["d"]))
+    np.testing.assert_allclose(dit.forward(wm, cm, xj, 400.0, ij["y"][0], ij["ctx"][0]),
+                               dit.forward(wj, cj, xj, 400.0, ij["y"][0], ij["ctx"][0]), rtol=1e-10, atol=1e-13)
+
+
 def test_forward_trajectories_are_independent_and_context_matters():
     cfg = workloads.get_config("cfg3_small")
     w = workloads.make_weights(cfg); inp = workloads.make_inputs(cfg, w)
