@@ -23,6 +23,7 @@ DESCRIPTIONS = {
     "cfg2": "diffusion-shaped group N=24->12 @ step 5 of 20 (DDIM eta=1), latent 4x64x64, DiT 1024 tok x 768 x 12 blocks, 77x768 cross-attention",
     "cfg3": "flow-shaped group N=48->32->16 @ steps 2,4 of 10, latent 16x64x64, DiT (1024+154) tok x 1536 x 24 blocks, joint attention",
     "cfg4": "8 prompts x N=48 (ragged 48->32->16, one group unpruned), cfg3 network, one packed batch",
+    "cfg3_mmdit": "cfg3 with dual-stream blocks (per-stream weights, RMS-normalised queries / keys): N=48->32->16 @ steps 2,4 of 10",
     "paper_std": "the paper's standard flow schedule N=48->24->12 @ steps 5,7 of 10 on the cfg3 network",
     "paper_flash": "the paper's efficiency schedule N=24->16->12 @ steps 5,7 of 10 on the cfg3 network",
 }

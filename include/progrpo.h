@@ -36,7 +36,7 @@ typedef enum {
 } pg_status;
 
 enum { PG_SAMPLER_FLOW = 0, PG_SAMPLER_DDIM = 1, PG_SAMPLER_TABLE = 2 };
-enum { PG_NET_NONE = 0, PG_NET_ADALN = 1, PG_NET_CROSS = 2, PG_NET_JOINT = 3 };
+enum { PG_NET_NONE = 0, PG_NET_ADALN = 1, PG_NET_CROSS = 2, PG_NET_JOINT = 3, PG_NET_MMDIT = 4 };
 
 /* Identifiers of the network tensors inside the flat bf16 weight buffer (see pg_weight_slot). */
 enum {
@@ -46,6 +46,10 @@ enum {
   PG_W_MOD_W, PG_W_MOD_B, PG_W_QKV_W, PG_W_QKV_B, PG_W_O_W, PG_W_O_B,
   PG_W_FC1_W, PG_W_FC1_B, PG_W_FC2_W, PG_W_FC2_B,
   PG_W_CQ_W, PG_W_CQ_B, PG_W_CKV_W, PG_W_CKV_B, PG_W_CO_W, PG_W_CO_B,
+  /* per block, dual-stream variant: the context stream's own tensors and the query / key norm scales */
+  PG_W_C_MOD_W, PG_W_C_MOD_B, PG_W_C_QKV_W, PG_W_C_QKV_B, PG_W_C_O_W, PG_W_C_O_B,
+  PG_W_C_FC1_W, PG_W_C_FC1_B, PG_W_C_FC2_W, PG_W_C_FC2_B,
+  PG_W_QN_G, PG_W_KN_G, PG_W_C_QN_G, PG_W_C_KN_G,
   PG_W_COUNT
 };
 
@@ -63,7 +67,10 @@ enum {
  *  Network: PG_NET_NONE (the caller writes u itself before pg_prune / pg_step) or a patch-2
  *  adaLN transformer of width D (multiple of 64), `blocks` blocks, `heads` heads (head width 32
  *  or 64), with Lc context tokens of width Dc (multiple of 64; CROSS: cross-attention sub-block,
- *  JOINT: context tokens appended to the image tokens).
+ *  JOINT: context tokens appended to the image tokens; MMDIT: as JOINT, but image and context
+ *  tokens keep separate streams with their own modulation, projection and MLP weights in every
+ *  block and meet only in the joint attention, whose queries and keys are RMS-normalised per
+ *  head (eps 1e-6) with a learnt scale per head channel).
  *  Schedule: n_sched entries (group, step, k): at `step`, group keeps k of its active
  *  trajectories (Sec. 5.2: counts strictly decrease along a group's entries, steps increase).
  *  Reward proxy (stand-in for Eq. 16): R = probe_bias + <probe_w, x_hat>.

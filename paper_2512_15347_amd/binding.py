@@ -22,11 +22,13 @@ _lib = C.CDLL(LIB_PATH)
 PG_OK, PG_EINVAL, PG_ESHAPE, PG_ENAN, PG_ESCHED, PG_EWORKSPACE, PG_EHIP = range(7)
 STATUS_NAMES = ["PG_OK", "PG_EINVAL", "PG_ESHAPE", "PG_ENAN", "PG_ESCHED", "PG_EWORKSPACE", "PG_EHIP"]
 PG_SAMPLER_FLOW, PG_SAMPLER_DDIM, PG_SAMPLER_TABLE = 0, 1, 2
-PG_NET_NONE, PG_NET_ADALN, PG_NET_CROSS, PG_NET_JOINT = 0, 1, 2, 3
+PG_NET_NONE, PG_NET_ADALN, PG_NET_CROSS, PG_NET_JOINT, PG_NET_MMDIT = 0, 1, 2, 3, 4
 
 WEIGHT_IDS = ["pe_w", "pe_b", "pos", "t_w1", "t_b1", "t_w2", "t_b2", "ctx_w", "ctx_b", "fmod_w", "fmod_b",
               "f_w", "f_b", "mod_w", "mod_b", "qkv_w", "qkv_b", "o_w", "o_b", "fc1_w", "fc1_b", "fc2_w",
-              "fc2_b", "cq_w", "cq_b", "ckv_w", "ckv_b", "co_w", "co_b"]
+              "fc2_b", "cq_w", "cq_b", "ckv_w", "ckv_b", "co_w", "co_b",
+              "c_mod_w", "c_mod_b", "c_qkv_w", "c_qkv_b", "c_o_w", "c_o_b", "c_fc1_w", "c_fc1_b", "c_fc2_w", "c_fc2_b",
+              "qn_g", "kn_g", "c_qn_g", "c_kn_g"]
 FIRST_BLOCK_ID = WEIGHT_IDS.index("mod_w")
 
 _dp = C.POINTER(C.c_double)
@@ -153,7 +155,8 @@ def make_config(cfg, probe_bias=0.0, adv_eps=1e-6, net=True, tables=None):
         c.sampler_kind = PG_SAMPLER_DDIM
         c.eta, c.beta0, c.beta1, c.T_train = float(s["eta"]), float(s["beta0"]), float(s["beta1"]), int(s["T_train"])
     if net:
-        c.net_kind = {"adaln": PG_NET_ADALN, "cross": PG_NET_CROSS, "joint": PG_NET_JOINT}[cfg["kind"]]
+        c.net_kind = {"adaln": PG_NET_ADALN, "cross": PG_NET_CROSS, "joint": PG_NET_JOINT,
+                      "mmdit": PG_NET_MMDIT}[cfg["kind"]]
         c.D, c.blocks, c.heads, c.Lc, c.Dc = (int(cfg[k]) for k in ("D", "blocks", "heads", "Lc", "Dc"))
     else:
         c.net_kind = PG_NET_NONE

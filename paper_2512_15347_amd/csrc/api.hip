@@ -119,7 +119,7 @@ static pg_status build_weight_layout(pg_ctx* c) {
   };
   put(PG_W_PE_W, D, C4); put(PG_W_PE_B, 1, D); put(PG_W_POS, c->Li, D);
   put(PG_W_T_W1, D, 256); put(PG_W_T_B1, 1, D); put(PG_W_T_W2, D, D); put(PG_W_T_B2, 1, D);
-  if (f.net_kind == PG_NET_JOINT) { put(PG_W_CTX_W, D, f.Dc); put(PG_W_CTX_B, 1, D); }
+  if (f.net_kind == PG_NET_JOINT || f.net_kind == PG_NET_MMDIT) { put(PG_W_CTX_W, D, f.Dc); put(PG_W_CTX_B, 1, D); }
   put(PG_W_FMOD_W, 2 * D, D); put(PG_W_FMOD_B, 1, 2 * D); put(PG_W_F_W, C4, D); put(PG_W_F_B, 1, C4);
   const int64_t block0 = off;
   put(PG_W_MOD_W, 6 * D, D); put(PG_W_MOD_B, 1, 6 * D); put(PG_W_QKV_W, 3 * D, D); put(PG_W_QKV_B, 1, 3 * D);
@@ -128,6 +128,13 @@ static pg_status build_weight_layout(pg_ctx* c) {
   if (f.net_kind == PG_NET_CROSS) {
     put(PG_W_CQ_W, D, D); put(PG_W_CQ_B, 1, D); put(PG_W_CKV_W, 2 * D, f.Dc); put(PG_W_CKV_B, 1, 2 * D);
     put(PG_W_CO_W, D, D); put(PG_W_CO_B, 1, D);
+  }
+  if (f.net_kind == PG_NET_MMDIT) {
+    const int hd = D / f.heads;
+    put(PG_W_C_MOD_W, 6 * D, D); put(PG_W_C_MOD_B, 1, 6 * D); put(PG_W_C_QKV_W, 3 * D, D); put(PG_W_C_QKV_B, 1, 3 * D);
+    put(PG_W_C_O_W, D, D); put(PG_W_C_O_B, 1, D); put(PG_W_C_FC1_W, 4 * D, D); put(PG_W_C_FC1_B, 1, 4 * D);
+    put(PG_W_C_FC2_W, D, 4 * D); put(PG_W_C_FC2_B, 1, D);
+    put(PG_W_QN_G, 1, hd); put(PG_W_KN_G, 1, hd); put(PG_W_C_QN_G, 1, hd); put(PG_W_C_KN_G, 1, hd);
   }
   c->block_stride = off - block0;
   c->weights_numel = block0 + c->block_stride * f.blocks;
@@ -159,7 +166,7 @@ static pg_status validate(const pg_config& f) {
     default: return fail(PG_EINVAL, "unknown sampler_kind %d", f.sampler_kind);
   }
   if (f.net_kind != PG_NET_NONE) {
-    if (f.net_kind < PG_NET_ADALN || f.net_kind > PG_NET_JOINT) return fail(PG_EINVAL, "unknown net_kind %d", f.net_kind);
+    if (f.net_kind < PG_NET_ADALN || f.net_kind > PG_NET_MMDIT) return fail(PG_EINVAL, "unknown net_kind %d", f.net_kind);
     if (f.D < 64 || f.D % 64) return fail(PG_ESHAPE, "width D = %d must be a positive multiple of 64", f.D);
     if (f.blocks < 1 || f.heads < 1 || f.D % f.heads) return fail(PG_ESHAPE, "heads must divide D, blocks >= 1");
     const int hd = f.D / f.heads;
@@ -241,7 +248,7 @@ extern "C" pg_status pg_create(const pg_config* cfg, pg_ctx** out) {
   const pg_config& f = c->cfg;
   c->d = f.C * f.H * f.W;
   c->Li = (f.H / 2) * (f.W / 2);
-  c->L = c->Li + (f.net_kind == PG_NET_JOINT ? f.Lc : 0);
+  c->L = c->Li + (f.net_kind == PG_NET_JOINT || f.net_kind == PG_NET_MMDIT ? f.Lc : 0);
   c->M0 = f.P * f.N;
   const int T = f.T;
   c->A.resize(T); c->B.resize(T); c->C.resize(T); c->Pv.resize(T); c->Qv.resize(T); c->tin.resize(T);

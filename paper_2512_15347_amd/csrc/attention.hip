@@ -236,7 +236,9 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(const AttnArg
   const float inv = 1.0f / l_tot;
   const int qr = q0 + l32;
   if (qr < a.Lq) {
-    uint16_t* op = a.out + ((int64_t)b * a.Lq + qr) * a.ldo + h * HD;
+    uint16_t* op = (a.split > 0) ? (qr < a.split ? a.out + ((int64_t)b * a.split + qr) * a.ldo + h * HD
+                                                 : a.out2 + ((int64_t)b * (a.Lq - a.split) + qr - a.split) * a.ldo + h * HD)
+                                 : a.out + ((int64_t)b * a.Lq + qr) * a.ldo + h * HD;
 #pragma unroll
     for (int ot = 0; ot < OT; ++ot)
 #pragma unroll

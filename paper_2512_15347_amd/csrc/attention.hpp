@@ -12,7 +12,8 @@ struct AttnArgs {
   const int32_t* kv_map;                          // batch -> key/value batch (NULL: identity)
   int B, Lq, Lk, heads;
   float scale_log2;                               // log2(e) / sqrt(hd)
-  int q_prescaled;                                // the producer of q has already multiplied it by scale_log2
+  int q_prescaled;
+  int split; uint16_t* out2;                      // split > 0: queries >= split go to out2[b * (Lq - split) + q - split, :]                                // the producer of q has already multiplied it by scale_log2
 };
 
 pg_status launch_attention(const AttnArgs& a, int hd, hipStream_t s);

@@ -1,11 +1,15 @@
 // The velocity / noise network evaluated on every active trajectory at every step (the drift input of
-// paper Eq. 12): a patch-2 adaLN transformer in three variants (conditioning vector only, extra
-// cross-attention over context tokens, context tokens joined to the sequence).  This file holds the
+// paper Eq. 12): a patch-2 adaLN transformer in four variants (conditioning vector only, extra
+// cross-attention over context tokens, context tokens joined to the sequence, and the dual-stream
+// form of the latter with per-stream weights and RMS-normalised queries / keys).  This file holds the
 // memory-bound glue kernels (patchify, conditioning GEMVs, LayerNorm + modulation, context rows) and
 // the orchestration; the contractions live in gemm.hip and attention.hip.
 //
 // Activation layout: rows r = m * L + token for the M active trajectories (image tokens first, then
-// context tokens in the joint variant).  The residual stream h is fp32; every GEMM operand is bf16.
+// context tokens in the joint variant).  The dual-stream variant keeps two planes instead, image rows
+// m * Li + t first and context rows M * Li + m * Lc + j behind them, so that each stream is one contiguous
+// GEMM operand; only q | k and V^T use the joint per-trajectory layout that attention reads.
+// The residual stream h is fp32; every GEMM operand is bf16.
 #include <cmath>
 #include "attention.hpp"
 #include "ctx.hpp"
@@ -168,9 +172,10 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restric
   }
 }
 
-// joint variant: h[m * L + Li + j, :] = ctx_h[group_of[m], j, :]
+// context rows of trajectory m: h[row_base + m * row_stride + j, :] = ctx_h[group_of[m], j, :]
 __global__ void scatter_context_kernel(const float* __restrict__ ctx_h, float* __restrict__ h,
-                                       const int32_t* __restrict__ group_of, int M, int L, int Li, int Lc, int D4) {
+                                       const int32_t* __restrict__ group_of, int M, int64_t row_base,
+                                       int row_stride, int Lc, int D4) {
   const int64_t total = (int64_t)M * Lc * D4;
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
@@ -178,7 +183,47 @@ __global__ void scatter_context_kernel(const float* __restrict__ ctx_h, float* _
   const int j = (int)((i / D4) % Lc);
   const int m = (int)(i / ((int64_t)D4 * Lc));
   const float4 v = reinterpret_cast<const float4*>(ctx_h)[((int64_t)group_of[m] * Lc + j) * D4 + k];
-  reinterpret_cast<float4*>(h)[((int64_t)m * L + Li + j) * D4 + k] = v;
+  reinterpret_cast<float4*>(h)[(row_base + (int64_t)m * row_stride + j) * D4 + k] = v;
+}
+
+// Dual-stream variant: queries and keys are RMS-normalised per head (eps 1e-6) and multiplied by a learnt
+// scale per head channel, in place on the joint q | k rows [R, 2D] (row r = m * L + t; t < Li: image
+// stream scales, else context stream scales); queries also take the softmax's log2(e)/sqrt(hd) here.
+// One wave per row, HD / 4 lanes per head chunk, 4 channels per lane.
+template <int HD>
+__global__ __launch_bounds__(256) void qk_norm_kernel(uint16_t* __restrict__ qk, int R, int L, int Li, int D,
+                                                      const uint16_t* __restrict__ gq_x, const uint16_t* __restrict__ gk_x,
+                                                      const uint16_t* __restrict__ gq_c, const uint16_t* __restrict__ gk_c,
+                                                      float q_mul) {
+  constexpr int LPH = HD / 4, HP = 64 / LPH;
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= R) return;
+  const bool img = (r % L) < Li;
+  const int sub = lane % LPH;
+  const int chunks = 2 * D / HD;
+  uint16_t* row = qk + (int64_t)r * 2 * D;
+  for (int c0 = 0; c0 < chunks; c0 += HP) {
+    const int ch = c0 + lane / LPH;
+    const bool ok = ch < chunks;
+    uint2 raw = {0u, 0u};
+    if (ok) raw = *reinterpret_cast<const uint2*>(row + (int64_t)ch * HD + sub * 4);
+    float x0 = bf2f((uint16_t)raw.x), x1 = bf2f((uint16_t)(raw.x >> 16)), x2 = bf2f((uint16_t)raw.y), x3 = bf2f((uint16_t)(raw.y >> 16));
+    float ss = (x0 * x0 + x1 * x1) + (x2 * x2 + x3 * x3);
+#pragma unroll
+    for (int o = 1; o < LPH; o <<= 1) ss += __shfl_xor(ss, o, WAVE);
+    if (!ok) continue;
+    const bool is_q = ch * HD < D;
+    const uint16_t* g = img ? (is_q ? gq_x : gk_x) : (is_q ? gq_c : gk_c);
+    const uint2 graw = *reinterpret_cast<const uint2*>(g + sub * 4);
+    const float m = rsqrtf(ss / (float)HD + 1e-6f) * (is_q ? q_mul : 1.0f);
+    x0 *= m * bf2f((uint16_t)graw.x); x1 *= m * bf2f((uint16_t)(graw.x >> 16));
+    x2 *= m * bf2f((uint16_t)graw.y); x3 *= m * bf2f((uint16_t)(graw.y >> 16));
+    uint2 pk;
+    pk.x = (uint32_t)f2bf(x0) | ((uint32_t)f2bf(x1) << 16);
+    pk.y = (uint32_t)f2bf(x2) | ((uint32_t)f2bf(x3) << 16);
+    *reinterpret_cast<uint2*>(row + (int64_t)ch * HD + sub * 4) = pk;
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -202,9 +247,9 @@ pg_status net_plan(pg_ctx* c) {
   n.att = take(R0 * D * 2);
   n.hid = take(R0 * 4 * D * 2);
   n.tok = take((size_t)c->M0 * c->Li * Kp * 2);
-  n.mod = take(((size_t)f.P * f.blocks * 6 * D + (size_t)f.P * 2 * D) * 4);
+  n.mod = take(((size_t)f.P * f.blocks * 6 * D * (f.net_kind == PG_NET_MMDIT ? 2 : 1) + (size_t)f.P * 2 * D) * 4);
   n.cond = take((256 + 2 * D + (size_t)f.P * D) * 4);
-  if (f.net_kind == PG_NET_JOINT) n.ctx_h = take((size_t)f.P * f.Lc * D * 4);
+  if (f.net_kind == PG_NET_JOINT || f.net_kind == PG_NET_MMDIT) n.ctx_h = take((size_t)f.P * f.Lc * D * 4);
   if (f.net_kind == PG_NET_CROSS) {
     n.ckv = take((size_t)f.blocks * f.P * f.Lc * D * 2);
     n.ckvt = take((size_t)f.blocks * f.P * D * Lcpad * 2);
@@ -232,7 +277,7 @@ pg_status net_prepare(pg_ctx* c, const uint16_t* weights, hipStream_t s) {
   const pg_config& f = c->cfg;
   Net n{c, s, (char*)c->buf.workspace + c->ws_net, weights};
   const int D = f.D;
-  if (f.net_kind == PG_NET_JOINT) {
+  if (f.net_kind == PG_NET_JOINT || f.net_kind == PG_NET_MMDIT) {
     GemmArgs g{};
     g.A = c->buf.ctx; g.lda = f.Dc; g.W = n.w(PG_W_CTX_W); g.ldw = n.ld(PG_W_CTX_W); g.bias = n.w(PG_W_CTX_B);
     g.M = f.P * f.Lc; g.N = D; g.K = f.Dc;
@@ -269,6 +314,9 @@ pg_status net_forward(pg_ctx* c, int step, const float* x_in, const uint16_t* we
   uint16_t* tok = n.at<uint16_t>(pl.tok);
   float* mod = n.at<float>(pl.mod);
   float* fmod = mod + (size_t)P * f.blocks * 6 * D;
+  float* cmod = fmod + (size_t)P * 2 * D;           // dual-stream variant: the context stream's modulation vectors
+  const bool dual = f.net_kind == PG_NET_MMDIT;
+  const int Rc = M * f.Lc;                          // context rows (dual-stream planes)
   float* emb = n.at<float>(pl.cond);
   float* t1 = emb + 256;
   float* c0 = t1 + D;
@@ -292,6 +340,12 @@ pg_status net_forward(pg_ctx* c, int step, const float* x_in, const uint16_t* we
       n.w(PG_W_MOD_W), n.ld(PG_W_MOD_W), c->block_stride, n.w(PG_W_MOD_B), c->block_stride, sc, D, mod, mod_ld, 6 * D,
       P, 6 * D, D);
   PG_LAUNCH_CHECK("gemv mod");
+  if (dual) {
+    gemv_bf16_kernel<false><<<dim3((6 * D + 3) / 4, f.blocks), dim3(256), 0, s>>>(
+        n.w(PG_W_C_MOD_W), n.ld(PG_W_C_MOD_W), c->block_stride, n.w(PG_W_C_MOD_B), c->block_stride, sc, D, cmod, mod_ld,
+        6 * D, P, 6 * D, D);
+    PG_LAUNCH_CHECK("gemv cmod");
+  }
   gemv_bf16_kernel<false><<<dim3((2 * D + 3) / 4, 1), dim3(256), 0, s>>>(n.w(PG_W_FMOD_W), n.ld(PG_W_FMOD_W), 0,
                                                                          n.w(PG_W_FMOD_B), 0, sc, D, fmod, 2 * D, 0, P,
                                                                          2 * D, D);
@@ -305,28 +359,93 @@ pg_status net_forward(pg_ctx* c, int step, const float* x_in, const uint16_t* we
     PG_LAUNCH_CHECK("patchify_kernel");
     GemmArgs g{};
     g.A = tok; g.lda = Kp; g.W = n.w(PG_W_PE_W); g.ldw = n.ld(PG_W_PE_W); g.bias = n.w(PG_W_PE_B);
-    g.M = Ri; g.N = D; g.K = Kp; g.k_algo = 4 * f.C; g.outf = h; g.ldo = D; g.L = L; g.Li = Li; g.pos = n.w(PG_W_POS);
+    g.M = Ri; g.N = D; g.K = Kp; g.k_algo = 4 * f.C; g.outf = h; g.ldo = D; g.L = dual ? Li : L; g.Li = Li; g.pos = n.w(PG_W_POS);
     PG_TRY(launch_gemm(g, EPI_EMBED, s));
   }
-  if (f.net_kind == PG_NET_JOINT) {
+  if (f.net_kind == PG_NET_JOINT || dual) {
     const int64_t total = (int64_t)M * f.Lc * (D / 4);
     scatter_context_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s>>>(
-        n.at<float>(pl.ctx_h), h, group_of, M, L, Li, f.Lc, D / 4);
+        n.at<float>(pl.ctx_h), h, group_of, M, dual ? (int64_t)Ri : (int64_t)Li, dual ? f.Lc : L, f.Lc, D / 4);
     PG_LAUNCH_CHECK("scatter_context_kernel");
   }
 
-  auto layer_norm = [&](const float* shift, const float* scale, int64_t ld, int rows_out, int L_out) -> pg_status {
+  // out[m * L_out + t, :] = bf16(LN(hin[m * L_in + t, :]) * (1 + scale) + shift), t < L_out
+  auto ln = [&](const float* hin, uint16_t* out, const float* shift, const float* scale, int64_t ld, int rows_out,
+                int L_in, int L_out) -> pg_status {
+    if (rows_out <= 0) return PG_OK;
     const dim3 grid((rows_out + 3) / 4), block(256);
-    if (D == 768) ln_modulate_kernel<3><<<grid, block, 0, s>>>(h, act, shift, scale, ld, group_of, rows_out, L, L_out, D);
-    else if (D == 1536) ln_modulate_kernel<6><<<grid, block, 0, s>>>(h, act, shift, scale, ld, group_of, rows_out, L, L_out, D);
-    else if (D == 1024) ln_modulate_kernel<4><<<grid, block, 0, s>>>(h, act, shift, scale, ld, group_of, rows_out, L, L_out, D);
-    else if (D == 256) ln_modulate_kernel<1><<<grid, block, 0, s>>>(h, act, shift, scale, ld, group_of, rows_out, L, L_out, D);
-    else ln_modulate_kernel<0><<<grid, block, 0, s>>>(h, act, shift, scale, ld, group_of, rows_out, L, L_out, D);
+    if (D == 768) ln_modulate_kernel<3><<<grid, block, 0, s>>>(hin, out, shift, scale, ld, group_of, rows_out, L_in, L_out, D);
+    else if (D == 1536) ln_modulate_kernel<6><<<grid, block, 0, s>>>(hin, out, shift, scale, ld, group_of, rows_out, L_in, L_out, D);
+    else if (D == 1024) ln_modulate_kernel<4><<<grid, block, 0, s>>>(hin, out, shift, scale, ld, group_of, rows_out, L_in, L_out, D);
+    else if (D == 256) ln_modulate_kernel<1><<<grid, block, 0, s>>>(hin, out, shift, scale, ld, group_of, rows_out, L_in, L_out, D);
+    else ln_modulate_kernel<0><<<grid, block, 0, s>>>(hin, out, shift, scale, ld, group_of, rows_out, L_in, L_out, D);
     PG_LAUNCH_CHECK("ln_modulate_kernel");
     return PG_OK;
   };
+  auto layer_norm = [&](const float* shift, const float* scale, int64_t ld, int rows_out, int L_out) -> pg_status {
+    return ln(h, act, shift, scale, ld, rows_out, dual ? L_out : L, L_out);
+  };
 
-  for (int b = 0; b < f.blocks; ++b) {
+  // ---- dual-stream blocks: two planes (image rows, context rows), joint q | k and V^T ----
+  if (dual) {
+    float* hs[2] = {h, h + (size_t)Ri * D};
+    uint16_t* acts[2] = {act, act + (size_t)Ri * D};
+    uint16_t* atts[2] = {att, att + (size_t)Ri * D};
+    uint16_t* hids[2] = {hid, hid + (size_t)Ri * 4 * D};
+    const int rows[2] = {Ri, Rc}, Ls[2] = {Li, f.Lc}, toff[2] = {0, Li};
+    const int W_MOD[2] = {PG_W_MOD_W, PG_W_C_MOD_W};
+    (void)W_MOD;
+    const int W_QKV[2] = {PG_W_QKV_W, PG_W_C_QKV_W}, B_QKV[2] = {PG_W_QKV_B, PG_W_C_QKV_B};
+    const int W_O[2] = {PG_W_O_W, PG_W_C_O_W}, B_O[2] = {PG_W_O_B, PG_W_C_O_B};
+    const int W_FC1[2] = {PG_W_FC1_W, PG_W_C_FC1_W}, B_FC1[2] = {PG_W_FC1_B, PG_W_C_FC1_B};
+    const int W_FC2[2] = {PG_W_FC2_W, PG_W_C_FC2_W}, B_FC2[2] = {PG_W_FC2_B, PG_W_C_FC2_B};
+    for (int b = 0; b < f.blocks; ++b) {
+      const float* mbs[2] = {mod + (size_t)b * 6 * D, cmod + (size_t)b * 6 * D};
+      for (int st = 0; st < 2; ++st) {
+        PG_TRY(ln(hs[st], acts[st], mbs[st], mbs[st] + D, mod_ld, rows[st], Ls[st], Ls[st]));
+        GemmArgs g{};
+        g.A = acts[st]; g.lda = D; g.W = n.w(W_QKV[st], b); g.ldw = n.ld(W_QKV[st]); g.bias = n.w(B_QKV[st], b);
+        g.M = rows[st]; g.N = 3 * D; g.K = D; g.outb = qk; g.ldob = 2 * D; g.vt = vt; g.v_start = 2 * D; g.Lpad = Lpad;
+        g.L = Ls[st]; g.Lout = L; g.tok_off = toff[st];
+        PG_TRY(launch_gemm(g, EPI_QKV, s));
+      }
+      {
+        const dim3 grid((R + 3) / 4), block(256);
+        if (hd == 64)
+          qk_norm_kernel<64><<<grid, block, 0, s>>>(qk, R, L, Li, D, n.w(PG_W_QN_G, b), n.w(PG_W_KN_G, b),
+                                                    n.w(PG_W_C_QN_G, b), n.w(PG_W_C_KN_G, b), scale_log2);
+        else
+          qk_norm_kernel<32><<<grid, block, 0, s>>>(qk, R, L, Li, D, n.w(PG_W_QN_G, b), n.w(PG_W_KN_G, b),
+                                                    n.w(PG_W_C_QN_G, b), n.w(PG_W_C_KN_G, b), scale_log2);
+        PG_LAUNCH_CHECK("qk_norm_kernel");
+      }
+      AttnArgs a{};
+      a.q = qk; a.ldq = 2 * D; a.k = qk + D; a.ldk = 2 * D; a.k_bstride = (int64_t)L * 2 * D;
+      a.vt = vt; a.vt_bstride = (int64_t)D * Lpad; a.Lkpad = Lpad; a.out = atts[0]; a.ldo = D;
+      a.split = Li; a.out2 = atts[1];
+      a.B = M; a.Lq = L; a.Lk = L; a.heads = f.heads; a.scale_log2 = scale_log2; a.q_prescaled = 1;
+      PG_TRY(launch_attention(a, hd, s));
+      for (int st = 0; st < 2; ++st) {
+        GemmArgs o{};
+        o.A = atts[st]; o.lda = D; o.W = n.w(W_O[st], b); o.ldw = n.ld(W_O[st]); o.bias = n.w(B_O[st], b);
+        o.M = rows[st]; o.N = D; o.K = D; o.outf = hs[st]; o.ldo = D; o.L = Ls[st]; o.gate = mbs[st] + 2 * D;
+        o.gate_ld = mod_ld; o.group_of = group_of;
+        PG_TRY(launch_gemm(o, EPI_RESID, s));
+        PG_TRY(ln(hs[st], acts[st], mbs[st] + 3 * D, mbs[st] + 4 * D, mod_ld, rows[st], Ls[st], Ls[st]));
+        GemmArgs g{};
+        g.A = acts[st]; g.lda = D; g.W = n.w(W_FC1[st], b); g.ldw = n.ld(W_FC1[st]); g.bias = n.w(B_FC1[st], b);
+        g.M = rows[st]; g.N = 4 * D; g.K = D; g.outb = hids[st]; g.ldob = 4 * D;
+        PG_TRY(launch_gemm(g, EPI_GELU, s));
+        GemmArgs o2{};
+        o2.A = hids[st]; o2.lda = 4 * D; o2.W = n.w(W_FC2[st], b); o2.ldw = n.ld(W_FC2[st]); o2.bias = n.w(B_FC2[st], b);
+        o2.M = rows[st]; o2.N = D; o2.K = 4 * D; o2.outf = hs[st]; o2.ldo = D; o2.L = Ls[st]; o2.gate = mbs[st] + 5 * D;
+        o2.gate_ld = mod_ld; o2.group_of = group_of;
+        PG_TRY(launch_gemm(o2, EPI_RESID, s));
+      }
+    }
+  }
+
+  for (int b = 0; b < (dual ? 0 : f.blocks); ++b) {
     const float* mb = mod + (size_t)b * 6 * D;     // shift1, scale1, gate1, shift2, scale2, gate2
     // attention sub-block
     PG_TRY(layer_norm(mb, mb + D, mod_ld, R, L));

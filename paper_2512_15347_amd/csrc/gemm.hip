@@ -333,7 +333,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
       // n .. n+3; they are stored as two bf16 pairs when they sit in one trajectory at an even offset
       const int Dv = MM;
       const int traj0 = n / a.L, tok0 = n - traj0 * a.L;
-      const bool whole = n + 3 < NN && tok0 + 3 < a.L && (tok0 & 1) == 0;
+      const bool whole = n + 3 < NN && tok0 + 3 < a.L && ((tok0 + a.tok_off) & 1) == 0;
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         const int slab0 = m0 + wm * (BM / WM) + i * 32;
@@ -352,7 +352,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
           const float bv = PB ? bf16_to_f32(PB[ch]) : 0.f;
           v.x += bv; v.y += bv; v.z += bv; v.w += bv;
           if (whole) {
-            uint32_t* dst = reinterpret_cast<uint32_t*>(a.vt + ((int64_t)traj0 * Dv + ch) * a.Lpad + tok0);
+            uint32_t* dst = reinterpret_cast<uint32_t*>(a.vt + ((int64_t)traj0 * Dv + ch) * a.Lpad + a.tok_off + tok0);
             const uint2 pk = pack_bf16x4(v);
             dst[0] = pk.x;
             dst[1] = pk.y;
@@ -363,7 +363,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
             for (int k = 0; k < 4; ++k) {
               if (n + k < NN) {
                 if (tok >= a.L) { tok -= a.L; ++traj; }
-                a.vt[((int64_t)traj * Dv + ch) * a.Lpad + tok] = f32_to_bf16(e[k]);
+                a.vt[((int64_t)traj * Dv + ch) * a.Lpad + a.tok_off + tok] = f32_to_bf16(e[k]);
                 ++tok;
               }
             }
@@ -442,8 +442,12 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
           float4 o = {v[p].x + bf16_to_f32((uint16_t)raw.x), v[p].y + bf16_to_f32((uint16_t)(raw.x >> 16)),
                       v[p].z + bf16_to_f32((uint16_t)raw.y), v[p].w + bf16_to_f32((uint16_t)(raw.y >> 16))};
           store_stream(a.outf + ((int64_t)traj * a.L + tok) * a.ldo + n, o);
-        } else if (EPI == EPI_BF16 || EPI == EPI_QKV) {
+        } else if (EPI == EPI_BF16) {
           store_stream(a.outb + (int64_t)r * a.ldob + n, pack_bf16x4(v[p]));
+        } else if (EPI == EPI_QKV) {
+          int64_t ro = r;
+          if (a.Lout > 0) { const int traj = r / a.L; ro = (int64_t)traj * a.Lout + a.tok_off + (r - traj * a.L); }
+          store_stream(a.outb + ro * a.ldob + n, pack_bf16x4(v[p]));
         } else if (EPI == EPI_GELU) {
           const float4 gl = {gelu_tanh(v[p].x), gelu_tanh(v[p].y), gelu_tanh(v[p].z), gelu_tanh(v[p].w)};
           store_stream(a.outb + (int64_t)r * a.ldob + n, pack_bf16x4(gl));

@@ -29,6 +29,7 @@ struct GemmArgs {
   uint16_t* vt; int v_start, Lpad;
   const float* gate; int64_t gate_ld; const int32_t* group_of;
   int Wp, HW, Wimg;                // unpatchify: patches per row, H*W, W
+  int Lout, tok_off;               // EPI_QKV: input row r = traj * L + tok is written as row traj * Lout + tok_off + tok (Lout 0: same row)
   float out_scale; int scale_cols; // EPI_BF16 / EPI_QKV: columns n < scale_cols are multiplied by out_scale (after the bias)
   int raster, group_m;             // tile order: XCD-aware remap on/off, tile rows per band (set by the launcher)
 };

@@ -189,6 +189,16 @@ def test_cfg3_full_size(lib):
 
 
 @pytest.mark.timeout(600)
+def test_cfg3_dual_stream_full_size(lib):
+    say("cfg3 network with dual-stream blocks, full size")
+    cfg, w, inp, tables, ctx, buf = _full(lib, "cfg3_mmdit")
+    _sampled_first_step(lib, cfg, w, inp, tables, ctx, buf, workloads.MASTER_SEED, [31])
+    xr, r0 = _free_run_properties(lib, cfg, ctx, buf, workloads.MASTER_SEED)
+    assert abs(r0 - sampler.linear_reward(xr, inp["probe_w"].astype(np.float64), inp["probe_b"])) < 1e-3
+    lib.pg_destroy(ctx)
+
+
+@pytest.mark.timeout(600)
 def test_cfg4_full_size(lib):
     say("cfg4 full size (8 groups, ragged, one unpruned)")
     cfg, w, inp, tables, ctx, buf = _full(lib, "cfg4")

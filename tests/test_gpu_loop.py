@@ -171,7 +171,7 @@ def _gpu_ctx(lib, cfg, w, inp):
     return ctx, buf
 
 
-@pytest.mark.parametrize("name", ["cfg1", "cfg2_small", "cfg3_small", "cfg4_small"])
+@pytest.mark.parametrize("name", ["cfg1", "cfg2_small", "cfg3_small", "cfg4_small", "cfg3_mmdit_small"])
 def test_network_output_at_step_0(lib, name):
     say(f"network forward {name}")
     seed = workloads.MASTER_SEED
@@ -189,7 +189,7 @@ def test_network_output_at_step_0(lib, name):
     lib.pg_destroy(ctx)
 
 
-@pytest.mark.parametrize("name", ["cfg1", "cfg2_small", "cfg3_small", "cfg4_small"])
+@pytest.mark.parametrize("name", ["cfg1", "cfg2_small", "cfg3_small", "cfg4_small", "cfg3_mmdit_small"])
 def test_full_loop_with_own_network(lib, name):
     """Free-running library loop against the free-running oracle: the survivor sets must be the
     oracle's (the seeds used here leave no near-tie), floats within the stated tolerances."""

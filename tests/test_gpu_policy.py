@@ -35,7 +35,7 @@ def _dev_weights(lib, ctx, cfg, w):
     return torch.from_numpy(lib.pack_weights(ctx, cfg, w).view(np.int16)).to(DEV)
 
 
-@pytest.mark.parametrize("name", ["cfg1", "cfg2_small", "cfg4_small"])
+@pytest.mark.parametrize("name", ["cfg1", "cfg2_small", "cfg4_small", "cfg3_mmdit_small"])
 def test_trajectory_record_and_policy_ratio(lib, name):
     say(f"policy ratio {name}")
     seed = 31
