@@ -186,46 +186,6 @@ __global__ void scatter_context_kernel(const float* __restrict__ ctx_h, float* _
   reinterpret_cast<float4*>(h)[(row_base + (int64_t)m * row_stride + j) * D4 + k] = v;
 }
 
-// Dual-stream variant: queries and keys are RMS-normalised per head (eps 1e-6) and multiplied by a learnt
-// scale per head channel, in place on the joint q | k rows [R, 2D] (row r = m * L + t; t < Li: image
-// stream scales, else context stream scales); queries also take the softmax's log2(e)/sqrt(hd) here.
-// One wave per row, HD / 4 lanes per head chunk, 4 channels per lane.
-template <int HD>
-__global__ __launch_bounds__(256) void qk_norm_kernel(uint16_t* __restrict__ qk, int R, int L, int Li, int D,
-                                                      const uint16_t* __restrict__ gq_x, const uint16_t* __restrict__ gk_x,
-                                                      const uint16_t* __restrict__ gq_c, const uint16_t* __restrict__ gk_c,
-                                                      float q_mul) {
-  constexpr int LPH = HD / 4, HP = 64 / LPH;
-  const int lane = threadIdx.x & 63;
-  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (r >= R) return;
-  const bool img = (r % L) < Li;
-  const int sub = lane % LPH;
-  const int chunks = 2 * D / HD;
-  uint16_t* row = qk + (int64_t)r * 2 * D;
-  for (int c0 = 0; c0 < chunks; c0 += HP) {
-    const int ch = c0 + lane / LPH;
-    const bool ok = ch < chunks;
-    uint2 raw = {0u, 0u};
-    if (ok) raw = *reinterpret_cast<const uint2*>(row + (int64_t)ch * HD + sub * 4);
-    float x0 = bf2f((uint16_t)raw.x), x1 = bf2f((uint16_t)(raw.x >> 16)), x2 = bf2f((uint16_t)raw.y), x3 = bf2f((uint16_t)(raw.y >> 16));
-    float ss = (x0 * x0 + x1 * x1) + (x2 * x2 + x3 * x3);
-#pragma unroll
-    for (int o = 1; o < LPH; o <<= 1) ss += __shfl_xor(ss, o, WAVE);
-    if (!ok) continue;
-    const bool is_q = ch * HD < D;
-    const uint16_t* g = img ? (is_q ? gq_x : gk_x) : (is_q ? gq_c : gk_c);
-    const uint2 graw = *reinterpret_cast<const uint2*>(g + sub * 4);
-    const float m = rsqrtf(ss / (float)HD + 1e-6f) * (is_q ? q_mul : 1.0f);
-    x0 *= m * bf2f((uint16_t)graw.x); x1 *= m * bf2f((uint16_t)(graw.x >> 16));
-    x2 *= m * bf2f((uint16_t)graw.y); x3 *= m * bf2f((uint16_t)(graw.y >> 16));
-    uint2 pk;
-    pk.x = (uint32_t)f2bf(x0) | ((uint32_t)f2bf(x1) << 16);
-    pk.y = (uint32_t)f2bf(x2) | ((uint32_t)f2bf(x3) << 16);
-    *reinterpret_cast<uint2*>(row + (int64_t)ch * HD + sub * 4) = pk;
-  }
-}
-
 // ------------------------------------------------------------------------------------------------
 
 static size_t a256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -393,8 +353,7 @@ pg_status net_forward(pg_ctx* c, int step, const float* x_in, const uint16_t* we
     uint16_t* atts[2] = {att, att + (size_t)Ri * D};
     uint16_t* hids[2] = {hid, hid + (size_t)Ri * 4 * D};
     const int rows[2] = {Ri, Rc}, Ls[2] = {Li, f.Lc}, toff[2] = {0, Li};
-    const int W_MOD[2] = {PG_W_MOD_W, PG_W_C_MOD_W};
-    (void)W_MOD;
+    const int W_QN[2] = {PG_W_QN_G, PG_W_C_QN_G}, W_KN[2] = {PG_W_KN_G, PG_W_C_KN_G};
     const int W_QKV[2] = {PG_W_QKV_W, PG_W_C_QKV_W}, B_QKV[2] = {PG_W_QKV_B, PG_W_C_QKV_B};
     const int W_O[2] = {PG_W_O_W, PG_W_C_O_W}, B_O[2] = {PG_W_O_B, PG_W_C_O_B};
     const int W_FC1[2] = {PG_W_FC1_W, PG_W_C_FC1_W}, B_FC1[2] = {PG_W_FC1_B, PG_W_C_FC1_B};
@@ -407,17 +366,10 @@ pg_status net_forward(pg_ctx* c, int step, const float* x_in, const uint16_t* we
         g.A = acts[st]; g.lda = D; g.W = n.w(W_QKV[st], b); g.ldw = n.ld(W_QKV[st]); g.bias = n.w(B_QKV[st], b);
         g.M = rows[st]; g.N = 3 * D; g.K = D; g.outb = qk; g.ldob = 2 * D; g.vt = vt; g.v_start = 2 * D; g.Lpad = Lpad;
         g.L = Ls[st]; g.Lout = L; g.tok_off = toff[st];
+        // queries and keys leave the projection RMS-normalised per head, queries also in the softmax's log2 units
+        g.norm_hd = hd; g.qn_g = n.w(W_QN[st], b); g.kn_g = n.w(W_KN[st], b);
+        g.out_scale = scale_log2; g.scale_cols = D;
         PG_TRY(launch_gemm(g, EPI_QKV, s));
-      }
-      {
-        const dim3 grid((R + 3) / 4), block(256);
-        if (hd == 64)
-          qk_norm_kernel<64><<<grid, block, 0, s>>>(qk, R, L, Li, D, n.w(PG_W_QN_G, b), n.w(PG_W_KN_G, b),
-                                                    n.w(PG_W_C_QN_G, b), n.w(PG_W_C_KN_G, b), scale_log2);
-        else
-          qk_norm_kernel<32><<<grid, block, 0, s>>>(qk, R, L, Li, D, n.w(PG_W_QN_G, b), n.w(PG_W_KN_G, b),
-                                                    n.w(PG_W_C_QN_G, b), n.w(PG_W_C_KN_G, b), scale_log2);
-        PG_LAUNCH_CHECK("qk_norm_kernel");
       }
       AttnArgs a{};
       a.q = qk; a.ldq = 2 * D; a.k = qk + D; a.ldk = 2 * D; a.k_bstride = (int64_t)L * 2 * D;

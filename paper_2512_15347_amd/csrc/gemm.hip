@@ -374,6 +374,12 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
     }
     const bool n_ok = n < NN;                        // N is a multiple of 4
     const float col_scale = n < a.scale_cols ? a.out_scale : 1.f;   // e.g. queries pre-multiplied by the softmax scale
+    float4 ng4 = {1.f, 1.f, 1.f, 1.f};               // norm scales of this lane's 4 columns
+    if (EPI == EPI_QKV && a.norm_hd > 0 && n_ok) {
+      const uint2 raw = *reinterpret_cast<const uint2*>((n < a.scale_cols ? a.qn_g : a.kn_g) + n % a.norm_hd);
+      ng4 = {bf16_to_f32((uint16_t)raw.x), bf16_to_f32((uint16_t)(raw.x >> 16)), bf16_to_f32((uint16_t)raw.y),
+             bf16_to_f32((uint16_t)(raw.y >> 16))};
+    }
     float4 b4 = {0.f, 0.f, 0.f, 0.f};
     if (PB && n_ok) {
       const uint2 raw = *reinterpret_cast<const uint2*>(PB + n);
@@ -395,6 +401,13 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
       for (int p = 0; p < NP; ++p) {
         v[p] = *reinterpret_cast<const float4*>(stg + (RPI * p + rsub) * EST + c4);
         v[p].x += b4.x; v[p].y += b4.y; v[p].z += b4.z; v[p].w += b4.w;
+        if (EPI == EPI_QKV && a.norm_hd > 0) {
+          // RMS norm over the head chunk this lane's 4 columns belong to (norm_hd / 4 adjacent lanes of the row)
+          float ss = (v[p].x * v[p].x + v[p].y * v[p].y) + (v[p].z * v[p].z + v[p].w * v[p].w);
+          for (int o = 1; o < a.norm_hd / 4; o <<= 1) ss += __shfl_xor(ss, o, 64);
+          const float rstd = rsqrtf(ss / (float)a.norm_hd + 1e-6f);
+          v[p].x *= rstd * ng4.x; v[p].y *= rstd * ng4.y; v[p].z *= rstd * ng4.z; v[p].w *= rstd * ng4.w;
+        }
         if (EPI == EPI_BF16 || EPI == EPI_QKV) { v[p].x *= col_scale; v[p].y *= col_scale; v[p].z *= col_scale; v[p].w *= col_scale; }
       }
       if (EPI == EPI_RESID) {
@@ -532,8 +545,9 @@ static int pick_tile(const GemmArgs& a, int epilogue) {
   };
   const double sc[6] = {score(256, 256, 1, 1.00), score(192, 256, 1, 0.97), score(128, 256, 1, 0.90),
                         score(128, 128, 2, 0.85), score(160, 256, 1, 0.92), score(224, 256, 1, 0.96)};
+  const bool wide_rows = epilogue == EPI_QKV && a.norm_hd > 32;   // the fused norm needs a whole head inside one wave's columns
   int best = 0;
-  for (int i = 1; i < 6; ++i) if (sc[i] > sc[best] * 1.02) best = i;
+  for (int i = 1; i < 6; ++i) if (sc[i] > sc[best] * 1.02 && !(wide_rows && i >= 4)) best = i;
   return best;
 }
 
@@ -577,6 +591,11 @@ pg_status launch_gemm(const GemmArgs& a_in, int epilogue, hipStream_t s) {
         (a.bias && ((uintptr_t)a.bias & 7)) || (a.gate && (a.gate_ld % 4 || ((uintptr_t)a.gate & 15))) ||
         (a.pos && ((uintptr_t)a.pos & 7)))
       return fail(PG_ESHAPE, "GEMM output / bias / gate rows need 16-byte (bf16: 8-byte) alignment");
+  }
+  if (epilogue == EPI_QKV && a.norm_hd > 0) {
+    if ((a.norm_hd != 32 && a.norm_hd != 64) || !a.qn_g || !a.kn_g || a.v_start % a.norm_hd || a.scale_cols % a.norm_hd ||
+        ((uintptr_t)a.qn_g & 7) || ((uintptr_t)a.kn_g & 7))
+      return fail(PG_ESHAPE, "GEMM: bad fused head norm (width %d)", a.norm_hd);
   }
   if (epilogue == EPI_QKV || epilogue == EPI_VT) {
     if (!a.vt || a.L < 1 || a.Lpad < a.L || (a.Lpad & 1) || ((uintptr_t)a.vt & 3) ||

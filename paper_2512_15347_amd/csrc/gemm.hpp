@@ -30,6 +30,7 @@ struct GemmArgs {
   const float* gate; int64_t gate_ld; const int32_t* group_of;
   int Wp, HW, Wimg;                // unpatchify: patches per row, H*W, W
   int Lout, tok_off;               // EPI_QKV: input row r = traj * L + tok is written as row traj * Lout + tok_off + tok (Lout 0: same row)
+  int norm_hd; const uint16_t* qn_g; const uint16_t* kn_g;   // EPI_QKV, norm_hd > 0: every norm_hd-wide head chunk of the row-major columns is RMS-normalised (eps 1e-6) and multiplied by the bf16 scales qn_g (columns < scale_cols) / kn_g [norm_hd]
   float out_scale; int scale_cols; // EPI_BF16 / EPI_QKV: columns n < scale_cols are multiplied by out_scale (after the bias)
   int raster, group_m;             // tile order: XCD-aware remap on/off, tile rows per band (set by the launcher)
 };
