@@ -236,6 +236,16 @@ pg_status pg_ovf_select(const float *rewards, const int32_t *group_offsets, cons
                         int32_t n_groups, uint64_t *masks, int32_t *sel_idx, int32_t *new_offsets,
                         int32_t *status, int32_t *scratch, void *stream);
 
+/* pg_ovf_select for groups of up to 1024 members (a generalisation: the paper's groups have at
+ * most 64).  masks: [n_groups, mask_words] uint64, bit i of word w = slot 64 w + i, groups must
+ * fit (size <= 64 * mask_words, 1 <= mask_words <= 16).  Same evaluation order, with the prefix
+ * sums over 64 zero-padded slots up to 64 members and over the next power of two above that, so
+ * groups of at most 64 members get exactly pg_ovf_select's answer. */
+pg_status pg_ovf_select_large(const float *rewards, const int32_t *group_offsets, const int32_t *k,
+                              int32_t n_groups, int32_t mask_words, uint64_t *masks,
+                              int32_t *sel_idx, int32_t *new_offsets, int32_t *status,
+                              int32_t *scratch, void *stream);
+
 /* Uniformly random k-subset per ragged group (the subsampling arm of Sec. 4.1), same outputs and
  * status convention as pg_ovf_select.  Slot j of group g draws one 32-bit key, word 0 of the
  * Philox-4x32-10 block with counter (j, draw, g, 2) and key (seed low, seed high); the k[g] slots

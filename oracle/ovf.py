@@ -17,6 +17,8 @@ bit for bit by any implementation that follows the same order):
   2. rank by (value ascending, original index ascending);
   3. fp64 prefix sums of y and y*y from the bottom (lo, lo2) and from the top
      (hi, hi2), each by the doubling recurrence over 64 zero-padded slots
+     (groups above 64 members, a generalisation beyond the paper's group sizes:
+     the next power of two)
      (a[i] += a[i-d] for d = 1, 2, 4, ..., 32, all i updated from the values of
      the previous pass);
   4. score D_j = k*(lo2[j] + hi2[k-j]) - (lo[j] + hi[k-j])^2  (= k^2 * variance),
@@ -52,11 +54,23 @@ def ovf_bruteforce(rewards, k):
     return best, best_set
 
 
+MAX_GROUP = 1024
+
+
+def scan_slots(n):
+    """Slots of the prefix-sum recurrence for a group of n: 64 up to 64 members (the
+    sampling loop's case), else the next power of two."""
+    s = WAVE
+    while s < n:
+        s *= 2
+    return s
+
+
 def _doubling_scan(a):
-    """Inclusive prefix sum of 64 fp64 slots by the doubling recurrence."""
+    """Inclusive prefix sum of len(a) (a power of two) fp64 slots by the doubling recurrence."""
     a = np.array(a, dtype=np.float64)
     d = 1
-    while d < WAVE:
+    while d < len(a):
         prev = a.copy()
         a[d:] = prev[d:] + prev[:-d]
         d *= 2
@@ -64,19 +78,22 @@ def _doubling_scan(a):
 
 
 def ovf_select(rewards, k):
-    """Exact variance-maximising k-subset of up to 64 fp32 rewards.
+    """Exact variance-maximising k-subset of up to MAX_GROUP fp32 rewards (the paper's
+    groups have at most 64 members; larger groups are a generalisation and use
+    scan_slots(n) zero-padded slots in step 3).
 
     Returns (mask as Python int, ascending list of selected original indices,
     j = how many were taken from the low end)."""
     r = np.asarray(rewards, dtype=np.float32)
     n = len(r)
-    if not (1 <= k <= n <= WAVE):
-        raise ValueError("need 1 <= k <= n <= 64")
+    if not (1 <= k <= n <= MAX_GROUP):
+        raise ValueError("need 1 <= k <= n <= %d" % MAX_GROUP)
+    S = scan_slots(n)
     if not np.all(np.isfinite(r)):
         raise FloatingPointError("non-finite reward")
     r = r + np.float32(0.0)                                   # -0.0 -> +0.0
     order = sorted(range(n), key=lambda i: (float(r[i]), i))   # step 2
-    y = np.zeros(WAVE); z = np.zeros(WAVE)
+    y = np.zeros(S); z = np.zeros(S)
     for rank, i in enumerate(order):
         y[rank] = float(r[i])                                  # ascending
         z[n - 1 - rank] = float(r[i])                          # descending
@@ -111,8 +128,29 @@ def ovf_groups(rewards, group_offsets, k_per_group):
     new_off = np.zeros(P + 1, dtype=np.int32)
     for g in range(P):
         b, e = int(group_offsets[g]), int(group_offsets[g + 1])
+        if e - b > WAVE:
+            raise ValueError("groups above 64 members need ovf_groups_large")
         m, idx, _ = ovf_select(rewards[b:e], int(k_per_group[g]))
         masks[g] = np.uint64(m)
+        sel.extend(b + i for i in idx)
+        new_off[g + 1] = new_off[g] + len(idx)
+    return masks, np.asarray(sel, dtype=np.int32), new_off
+
+
+def ovf_groups_large(rewards, group_offsets, k_per_group, mask_words):
+    """As ovf_groups for groups of up to MAX_GROUP members: masks is uint64[P, mask_words],
+    bit i of word w = slot 64 w + i."""
+    P = len(k_per_group)
+    masks = np.zeros((P, mask_words), dtype=np.uint64)
+    sel = []
+    new_off = np.zeros(P + 1, dtype=np.int32)
+    for g in range(P):
+        b, e = int(group_offsets[g]), int(group_offsets[g + 1])
+        if e - b > 64 * mask_words:
+            raise ValueError("group does not fit the mask")
+        m, idx, _ = ovf_select(rewards[b:e], int(k_per_group[g]))
+        for w in range(mask_words):
+            masks[g, w] = np.uint64((m >> (64 * w)) & 0xFFFFFFFFFFFFFFFF)
         sel.extend(b + i for i in idx)
         new_off[g + 1] = new_off[g] + len(idx)
     return masks, np.asarray(sel, dtype=np.int32), new_off

@@ -103,6 +103,109 @@ __global__ __launch_bounds__(OVF_WAVES * WAVE) void ovf_select_kernel(
   if (lane == 0) masks[g] = mask;
 }
 
+// ---- the same selection for groups of up to 1024 members (beyond the paper's group sizes): one
+// workgroup of 1024 lanes per group, one member per lane.  Same evaluation order as above with the
+// prefix sums taken over S zero-padded slots, S = 64 up to 64 members, else the next power of two.
+constexpr int OVF_LARGE = 1024;
+
+__global__ __launch_bounds__(OVF_LARGE) void ovf_select_large_kernel(
+    const float* __restrict__ rewards, const int32_t* __restrict__ offsets, const int32_t* __restrict__ kk,
+    int n_groups, const int32_t* __restrict__ new_offsets, int mask_words, uint64_t* __restrict__ masks,
+    int32_t* __restrict__ sel_idx, int32_t* __restrict__ status) {
+  __shared__ float val[OVF_LARGE];
+  __shared__ float sorted[OVF_LARGE];
+  __shared__ double sc[4][OVF_LARGE];              // running sums of y, y^2, z, z^2
+  __shared__ double red_s[OVF_LARGE / WAVE];
+  __shared__ int red_b[OVF_LARGE / WAVE];
+  __shared__ int wave_cnt[OVF_LARGE / WAVE];
+  const int tid = threadIdx.x, lane = tid & (WAVE - 1), wv = tid / WAVE;
+  const int g = blockIdx.x;
+  const int b = offsets[g];
+  const int n = offsets[g + 1] - b;
+  const int k = kk[g];
+  const int out0 = new_offsets[g];
+  uint64_t* mrow = masks + (int64_t)g * mask_words;
+  if (n < 1 || n > OVF_LARGE || n > 64 * mask_words || k < 1 || k > n) {
+    if (tid == 0 && !(n == 0 && k == 0)) atomicOr(status, 2);
+    if (tid < mask_words) mrow[tid] = 0ull;
+    return;                                          // whole workgroup leaves together
+  }
+  const bool live = tid < n;
+  const float v = live ? rewards[b + tid] + 0.0f : 0.0f;
+  const bool bad = live && !(__builtin_fabsf(v) <= 3.4028234663852886e38f);
+  const int any_bad = __syncthreads_or(bad ? 1 : 0);
+  bool keep;
+  if (any_bad || k == n) {
+    if (any_bad && tid == 0) atomicOr(status, 1);
+    keep = tid < k;
+  } else {
+    val[tid] = v;
+    __syncthreads();
+    int rank = 0;
+    if (live)
+      for (int l = 0; l < n; ++l) {
+        const float vl = val[l];
+        rank += (vl < v || (vl == v && l < tid)) ? 1 : 0;
+      }
+    sorted[tid] = 0.0f;
+    __syncthreads();
+    if (live) sorted[rank] = v;
+    __syncthreads();
+    int S = WAVE;
+    while (S < n) S <<= 1;
+    {
+      const double y = (double)sorted[tid];
+      const double z = live ? (double)sorted[n - 1 - tid] : 0.0;
+      sc[0][tid] = y; sc[1][tid] = __dmul_rn(y, y); sc[2][tid] = z; sc[3][tid] = __dmul_rn(z, z);
+    }
+    __syncthreads();
+    for (int dd = 1; dd < S; dd <<= 1) {             // all slots updated from the values of the previous pass
+      double t[4] = {0.0, 0.0, 0.0, 0.0};
+      if (tid >= dd && tid < S)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) t[q] = sc[q][tid - dd];
+      __syncthreads();
+      if (tid >= dd && tid < S)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) sc[q][tid] = __dadd_rn(sc[q][tid], t[q]);
+      __syncthreads();
+    }
+    // candidate j = tid (0 <= j <= k): j lowest + (k - j) highest
+    const int j = tid, m = k - j;
+    double score = -__builtin_huge_val();
+    int best = j;
+    if (j <= k) {
+      const double lo = j ? sc[0][j - 1] : 0.0, lo2 = j ? sc[1][j - 1] : 0.0;
+      const double hi = m ? sc[2][m - 1] : 0.0, hi2 = m ? sc[3][m - 1] : 0.0;
+      const double s1 = __dadd_rn(lo, hi), s2 = __dadd_rn(lo2, hi2);
+      score = __dsub_rn(__dmul_rn((double)k, s2), __dmul_rn(s1, s1));
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {               // arg-max, ties to the smaller j
+      const double os = __shfl_xor(score, o, WAVE);
+      const int ob = __shfl_xor(best, o, WAVE);
+      if (os > score || (os == score && ob < best)) { score = os; best = ob; }
+    }
+    if (lane == 0) { red_s[wv] = score; red_b[wv] = best; }
+    __syncthreads();
+    score = red_s[0]; best = red_b[0];
+    for (int w = 1; w < OVF_LARGE / WAVE; ++w)
+      if (red_s[w] > score || (red_s[w] == score && red_b[w] < best)) { score = red_s[w]; best = red_b[w]; }
+    keep = live && (rank < best || rank >= n - (k - best));
+  }
+  const uint64_t ballot = __ballot(keep);
+  if (lane == 0) {
+    wave_cnt[wv] = __popcll(ballot);
+    if (wv < mask_words) mrow[wv] = ballot;
+  }
+  __syncthreads();
+  if (keep) {
+    int before = 0;
+    for (int w = 0; w < wv; ++w) before += wave_cnt[w];
+    sel_idx[out0 + before + __popcll(ballot & ((1ull << lane) - 1ull))] = b + tid;
+  }
+}
+
 // ---- exclusive scan of k over groups (new_offsets[g] = sum of k[0..g)) in three launches ----
 __global__ __launch_bounds__(SCAN_THREADS) void scan_block_sums_kernel(const int32_t* __restrict__ kk,
                                                                        int n, int32_t* __restrict__ sums) {
@@ -389,5 +492,22 @@ extern "C" pg_status pg_group_stats(const float* rewards, const int32_t* group_o
   group_stats_kernel<<<dim3((n_groups + OVF_WAVES - 1) / OVF_WAVES), dim3(OVF_WAVES * WAVE), 0,
                        (hipStream_t)stream>>>(rewards, group_offsets, n_groups, delta, sigma, clustered_share);
   PG_LAUNCH_CHECK("group_stats_kernel");
+  return PG_OK;
+}
+
+extern "C" pg_status pg_ovf_select_large(const float* rewards, const int32_t* group_offsets, const int32_t* k,
+                                         int32_t n_groups, int32_t mask_words, uint64_t* masks, int32_t* sel_idx,
+                                         int32_t* new_offsets, int32_t* status, int32_t* scratch, void* stream) {
+  if (n_groups < 0) return fail(PG_EINVAL, "pg_ovf_select_large: n_groups = %d", n_groups);
+  if (mask_words < 1 || mask_words > OVF_LARGE / WAVE)
+    return fail(PG_EINVAL, "pg_ovf_select_large: mask_words = %d (1..%d)", mask_words, OVF_LARGE / WAVE);
+  if (n_groups == 0) return PG_OK;
+  if (!rewards || !group_offsets || !k || !masks || !sel_idx || !new_offsets || !status || !scratch)
+    return fail(PG_EINVAL, "pg_ovf_select_large: null pointer");
+  hipStream_t s = (hipStream_t)stream;
+  PG_TRY(scan_k(k, n_groups, scratch, new_offsets, s));
+  ovf_select_large_kernel<<<dim3(n_groups), dim3(OVF_LARGE), 0, s>>>(rewards, group_offsets, k, n_groups, new_offsets,
+                                                                      mask_words, masks, sel_idx, status);
+  PG_LAUNCH_CHECK("ovf_select_large_kernel");
   return PG_OK;
 }

@@ -172,6 +172,51 @@ def test_ovf_ragged_groups_ties_and_degenerate_k(lib):
     np.testing.assert_array_equal(newoff, w_off)
 
 
+def test_ovf_groups_above_64_members(lib):
+    """Groups of up to 1024 members (one workgroup per group), ragged, with ties, bit for bit against the
+    oracle; groups of at most 64 members must get the 64-slot routine's answer."""
+    say("ovf large groups")
+    rng = np.random.default_rng(21)
+    sizes = [1024, 65, 100, 513, 64, 48, 1, 777, 200, 1000, 129, 2]
+    ks =    [512, 7, 50, 40, 16, 24, 1, 776, 200, 1, 64, 1]
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    r = (rng.standard_normal(off[-1]) * np.where(rng.random(off[-1]) < 0.8, 0.05, 1.0)).astype(np.float32)
+    r[off[2]:off[3]] = np.round(r[off[2]:off[3]] * 4) / 4         # many exact ties
+    r[off[10]:off[11]] = -1.5                                      # all equal
+    words = 16
+    w_masks, w_sel, w_off = ovf.ovf_groups_large(r, off, ks, words)
+    P = len(sizes)
+    masks = torch.full((P, words), -1, dtype=torch.int64, device=DEV)
+    sel = torch.full((int(np.sum(ks)),), -1, dtype=torch.int32, device=DEV)
+    noff = torch.zeros(P + 1, dtype=torch.int32, device=DEV)
+    status = torch.zeros(4, dtype=torch.int32, device=DEV)
+    scratch = torch.zeros(lib.pg_ovf_scratch_ints(P), dtype=torch.int32, device=DEV)
+    lib.pg_ovf_select_large(torch.from_numpy(r).to(DEV), torch.from_numpy(off).to(DEV),
+                            torch.tensor(ks, dtype=torch.int32, device=DEV), P, words, masks, sel, noff, status, scratch)
+    torch.cuda.synchronize()
+    assert status[0].item() == 0
+    np.testing.assert_array_equal(masks.cpu().numpy().view(np.uint64), w_masks)
+    np.testing.assert_array_equal(noff.cpu().numpy(), w_off)
+    np.testing.assert_array_equal(sel.cpu().numpy(), w_sel)
+    # the small groups agree with the one-wave kernel
+    for g in (4, 5, 6, 11):
+        m64, _, _ = ovf.ovf_groups(r[off[g]:off[g + 1]], [0, sizes[g]], [ks[g]])
+        assert int(w_masks[g, 0]) == int(m64[0])
+    # a group that does not fit the mask, a bad k and a non-finite reward are flagged
+    off2 = torch.tensor([0, 200, 210, 300], dtype=torch.int32, device=DEV)
+    k2 = torch.tensor([5, 11, 3], dtype=torch.int32, device=DEV)
+    r2 = torch.from_numpy(r[:300].copy()).to(DEV); r2[250] = float("inf")
+    masks2 = torch.full((3, 2), -1, dtype=torch.int64, device=DEV)
+    sel2 = torch.full((19,), -1, dtype=torch.int32, device=DEV)
+    status.zero_()
+    lib.pg_ovf_select_large(r2, off2, k2, 3, 2, masks2, sel2, noff[:4], status, scratch)
+    torch.cuda.synchronize()
+    assert status[0].item() == 3
+    m2 = masks2.cpu().numpy().view(np.uint64)
+    assert not m2[0].any() and not m2[1].any() and int(m2[2, 0]) == 0b111
+    assert sel2.cpu().numpy()[16:].tolist() == [210, 211, 212]
+
+
 def test_ovf_many_groups_and_schedule_sizes(lib):
     say("ovf 20000 groups")
     rng = np.random.default_rng(9)

@@ -105,7 +105,41 @@ def test_rejects_bad_input():
     with pytest.raises(ValueError):
         ovf.ovf_select(np.zeros(3, np.float32), 0)
     with pytest.raises(ValueError):
-        ovf.ovf_select(np.zeros(65, np.float32), 4)
+        ovf.ovf_select(np.zeros(1025, np.float32), 4)
+    with pytest.raises(ValueError):
+        ovf.ovf_groups(np.zeros(65, np.float32), [0, 65], [4])
+
+
+def test_groups_above_64_members():
+    """Generalisation beyond the paper's group sizes.  Pins: the chosen set beats every "j lowest + k-j highest"
+    candidate evaluated in exact rational arithmetic (an arithmetic path of its own), no single swap with an
+    unselected member raises the variance (necessary for the optimum of Eq. 10), and up to 64 members the
+    result is what the 64-slot routine gave before."""
+    from fractions import Fraction
+    rng = np.random.default_rng(12)
+    for n, k in ((65, 7), (100, 50), (200, 77), (513, 40), (1024, 512)):
+        r = (rng.standard_normal(n) * np.where(rng.random(n) < 0.8, 0.05, 1.0)).astype(np.float32)
+        mask, idx, j = ovf.ovf_select(r, k)
+        assert len(idx) == k and bin(mask).count("1") == k and idx == sorted(idx)
+        fr = sorted(Fraction(float(v)) for v in r)
+        def score(jj):
+            sub = fr[:jj] + fr[n - (k - jj):]
+            s1 = sum(sub); s2 = sum(v * v for v in sub)
+            return k * s2 - s1 * s1
+        best = max(range(k + 1), key=lambda jj: (score(jj), -jj))
+        chosen = sorted(Fraction(float(r[i])) for i in idx)
+        assert chosen == fr[:best] + fr[n - (k - best):]
+        var_sel = np.var(r[idx].astype(np.float64))
+        inside = set(idx)
+        outside = [i for i in range(n) if i not in inside]
+        for _ in range(300):
+            a = idx[rng.integers(k)]; b = outside[rng.integers(n - k)]
+            trial = [i for i in idx if i != a] + [b]
+            assert np.var(r[trial].astype(np.float64)) <= var_sel * (1 + 1e-12)
+    masks, sel, off = ovf.ovf_groups_large(np.arange(300, dtype=np.float32), [0, 100, 300], [3, 130], 4)
+    assert masks.shape == (2, 4) and off.tolist() == [0, 3, 133]
+    assert sum(bin(int(w)).count("1") for w in masks[1]) == 130 and int(masks[0, 2]) == 0
+    assert sel[:3].tolist() in ([0, 98, 99], [0, 1, 99])
 
 
 def test_groups_compaction_and_schedule_counts():
