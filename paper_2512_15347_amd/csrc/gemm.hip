@@ -99,12 +99,10 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) { return __builtin_bit_
 
 template <int EPI, int BM, int BN, int BK, int WM, int WN, int MINW, int NST>
 __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs a) {
-  constexpr bool DMA = NST > 0;                    // NST LDS stages filled by direct loads; 0: register staging
-  constexpr int THREADS = 64 * WM * WN;
+  static_assert(NST >= 2, "LDS stages filled by direct loads");
   constexpr int CH = BK / 8;                       // 16-byte chunks per tile row
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;   // 32x32 MFMA tiles per wave
   constexpr int A_BYTES = BM * BK * 2, W_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + W_BYTES;
-  constexpr int A_LD = BM * CH / THREADS, W_LD = BN * CH / THREADS;   // chunks staged per lane
   extern __shared__ __align__(16) unsigned char smem[];
   // ---- the problem this block works on.  Value channels (EPI_VT, and the columns >= v_start of
   // EPI_QKV) are produced TRANSPOSED by swapping the operand roles: rows of the block's problem are
@@ -161,28 +159,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   const int nk = a.K / BK;
-  // One K step of MFMAs from LDS stage `stage`; `between(ks)` runs after the operand reads of slab ks
-  // have been issued and before its MFMAs (the direct-load path spreads its requests there).
-  auto multiply_stage = [&](int stage, auto&& between) {
-    const unsigned char* sA = smem + stage * STAGE_BYTES;
-    const unsigned char* sW = sA + A_BYTES;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 af[TM], wf[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const bf16x8*>(sA + lds_off<CH>(a_row[i], 2 * ks + half));
-#pragma unroll
-      for (int j = 0; j < TN; ++j) wf[j] = *reinterpret_cast<const bf16x8*>(sW + lds_off<CH>(w_row[j], 2 * ks + half));
-      between(ks);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], wf[j], acc[i][j], 0, 0, 0);
-    }
-  };
-
-  if constexpr (DMA) {
+  {
     // ---- global -> LDS directly: every wave owns N_REG / WAVES regions of 1 KB (64 / CH tile rows) ----
     constexpr int WAVES = WM * WN, RPR = 64 / CH;
     constexpr int A_REG = BM / RPR, N_REG = (BM + BN) / RPR, PER_WAVE = (N_REG + WAVES - 1) / WAVES;
@@ -270,50 +247,6 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
             ++q;
           }
       }
-    }
-  } else {
-    // ---- global -> registers -> LDS ----
-    static_assert(BM * CH % THREADS == 0 && BN * CH % THREADS == 0, "staging must divide evenly");
-    const uint16_t* a_ptr[A_LD];
-    const uint16_t* w_ptr[W_LD];
-    int a_st[A_LD], w_st[W_LD];
-#pragma unroll
-    for (int i = 0; i < A_LD; ++i) {
-      const int c = tid + i * THREADS, row = c / CH, ch = c % CH;
-      a_ptr[i] = PA + (int64_t)min(m0 + row, MM - 1) * LDA + ch * 8;
-      a_st[i] = lds_off<CH>(row, ch);
-    }
-#pragma unroll
-    for (int i = 0; i < W_LD; ++i) {
-      const int c = tid + i * THREADS, row = c / CH, ch = c % CH;
-      w_ptr[i] = PW + (int64_t)min(n0 + row, NN - 1) * LDW + ch * 8;
-      w_st[i] = A_BYTES + lds_off<CH>(row, ch);
-    }
-    u32x4v ra[A_LD], rw[W_LD];
-    auto load_regs = [&](int kt) {
-#pragma unroll
-      for (int i = 0; i < A_LD; ++i) ra[i] = *reinterpret_cast<const u32x4v*>(a_ptr[i] + kt * BK);
-#pragma unroll
-      for (int i = 0; i < W_LD; ++i) rw[i] = *reinterpret_cast<const u32x4v*>(w_ptr[i] + kt * BK);
-    };
-    auto store_regs = [&](int stage) {
-      unsigned char* d = smem + stage * STAGE_BYTES;
-#pragma unroll
-      for (int i = 0; i < A_LD; ++i) *reinterpret_cast<u32x4v*>(d + a_st[i]) = ra[i];
-#pragma unroll
-      for (int i = 0; i < W_LD; ++i) *reinterpret_cast<u32x4v*>(d + w_st[i]) = rw[i];
-    };
-    load_regs(0);
-    store_regs(0);
-    if (nk > 1) load_regs(1);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-      // registers hold tile kt+1: park it in the other stage (last read before the previous barrier),
-      // then start fetching tile kt+2 so that a whole iteration hides its latency
-      if (kt + 1 < nk) store_regs((kt + 1) & 1);
-      if (kt + 2 < nk) load_regs(kt + 2);
-      multiply_stage(kt & 1, [](int) {});
-      __syncthreads();
     }
   }
 
@@ -508,7 +441,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
 
 template <int EPI, int BM, int BN, int BK, int WM, int WN, int MINW, int NST>
 static pg_status launch_tile(const GemmArgs& a, hipStream_t s) {
-  constexpr int LDS = (NST > 0 ? NST : 2) * (BM + BN) * BK * 2;
+  constexpr int LDS = NST * (BM + BN) * BK * 2;
   static bool attr_set = false;
   if (!attr_set) {
     PG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel<EPI, BM, BN, BK, WM, WN, MINW, NST>),
@@ -529,7 +462,7 @@ static pg_status launch_tile(const GemmArgs& a, hipStream_t s) {
 // Tile choice.  A launch runs in rounds of 256 concurrent workgroups (one per compute unit); the last
 // round is usually part empty, and with few K steps a tile's fixed prologue / epilogue weighs more.
 // Pick the shape with the best product of slot occupancy and the measured relative speed of its main
-// loop.  PROGRPO_GEMM_TILE (0..3) overrides the heuristic; it is a tuning aid.
+// loop.  PROGRPO_GEMM_TILE (0..5) overrides the heuristic; it is a tuning aid.
 static int pick_tile(const GemmArgs& a, int epilogue) {
   static const int forced = [] { const char* e = getenv("PROGRPO_GEMM_TILE"); return e ? atoi(e) : -1; }();
   if (forced >= 0 && forced <= 5) return forced;
@@ -553,23 +486,13 @@ static int pick_tile(const GemmArgs& a, int epilogue) {
 
 template <int EPI>
 static pg_status launch_one(const GemmArgs& a, hipStream_t s) {
-  static const bool dma = [] { const char* e = getenv("PROGRPO_GEMM_STAGING"); return !(e && e[0] == 'r'); }();
-  if (dma) {
-    switch (pick_tile(a, EPI)) {
-      case 0: return launch_tile<EPI, 256, 256, 64, 2, 4, 2, 2>(a, s);
-      case 1: return launch_tile<EPI, 192, 256, 64, 2, 4, 2, 2>(a, s);
-      case 2: return launch_tile<EPI, 128, 256, 64, 2, 4, 2, 2>(a, s);
-      case 3: return launch_tile<EPI, 128, 128, 64, 2, 2, 2, 2>(a, s);
-      case 4: return launch_tile<EPI, 160, 256, 64, 1, 8, 2, 2>(a, s);     // heights that are not a multiple of 64:
-      default: return launch_tile<EPI, 224, 256, 64, 1, 8, 2, 2>(a, s);    // one wave row, 32 columns per wave
-    }
-  }
-  switch (pick_tile(a, EPI)) {      // PROGRPO_GEMM_STAGING=regs: staging through registers (tuning aid)
-    case 0: return launch_tile<EPI, 256, 256, 64, 2, 4, 2, 0>(a, s);
-    case 1: return launch_tile<EPI, 192, 256, 64, 2, 4, 2, 0>(a, s);
-    case 2: return launch_tile<EPI, 128, 256, 64, 2, 4, 2, 0>(a, s);
-    case 3: return launch_tile<EPI, 128, 128, 64, 2, 2, 2, 0>(a, s);
-    default: return launch_tile<EPI, 256, 256, 64, 2, 4, 2, 0>(a, s);
+  switch (pick_tile(a, EPI)) {
+    case 0: return launch_tile<EPI, 256, 256, 64, 2, 4, 2, 2>(a, s);
+    case 1: return launch_tile<EPI, 192, 256, 64, 2, 4, 2, 2>(a, s);
+    case 2: return launch_tile<EPI, 128, 256, 64, 2, 4, 2, 2>(a, s);
+    case 3: return launch_tile<EPI, 128, 128, 64, 2, 2, 2, 2>(a, s);
+    case 4: return launch_tile<EPI, 160, 256, 64, 1, 8, 2, 2>(a, s);     // heights that are not a multiple of 64:
+    default: return launch_tile<EPI, 224, 256, 64, 1, 8, 2, 2>(a, s);    // one wave row, 32 columns per wave
   }
 }
 
