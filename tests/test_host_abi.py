@@ -23,6 +23,27 @@ def test_exports_match_header():
         assert hasattr(lib, name), name
 
 
+def test_header_is_plain_c_and_matches_the_binding_structs(tmp_path):
+    """include/progrpo.h compiles as C99 and as C++17, and the struct sizes the binding marshals are the
+    compiler's."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no host C compiler")
+    src = tmp_path / "abi.c"
+    src.write_text('#include <stdio.h>\n#include "progrpo.h"\n'
+                   'int main(void) { printf("%zu %zu %d\\n", sizeof(pg_config), sizeof(pg_buffers), (int)PG_W_COUNT); return 0; }\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.check_call([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, str(src), "-o", str(tmp_path / "abi")])
+    out = subprocess.check_output([str(tmp_path / "abi")]).decode().split()
+    assert int(out[0]) == C.sizeof(pg.pg_config) and int(out[1]) == C.sizeof(pg.pg_buffers)
+    assert int(out[2]) == len(pg.WEIGHT_IDS)
+    gxx = shutil.which("g++")
+    if gxx:
+        subprocess.check_call([gxx, "-std=c++17", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)])
+
+
 def _ctx(name, **kw):
     cfg = workloads.get_config(name)
     c, keep = pg.make_config(cfg, **kw)
@@ -105,7 +126,7 @@ def test_ddim_needs_enough_training_steps_and_eta():
 
 
 def test_weight_layout_is_disjoint_and_covers_all_tensors():
-    for name in ("cfg1", "cfg2_small", "cfg3_small"):
+    for name in ("cfg1", "cfg2_small", "cfg3_small", "cfg3_mmdit_small"):
         cfg, c, keep = _ctx(name)
         ctx = pg.pg_create(c)
         top, blk = workloads.weight_shapes(cfg)
