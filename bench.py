@@ -216,6 +216,8 @@ def main():
 
     import numpy as np
     import torch
+    from paper_2512_15347_amd.build import ensure_built
+    ensure_built()
     from paper_2512_15347_amd import binding as pg, workloads
 
     cfg = workloads.get_config(args.workload)

@@ -44,5 +44,11 @@ def build(verbose=True, jobs=4):
     return LIB
 
 
+def ensure_built():
+    """Build only if no library is there (tests, the smoke run and the benchmark load what is built)."""
+    if not os.path.exists(os.environ.get("PROGRPO_LIB", LIB)):
+        build(verbose=False)
+
+
 if __name__ == "__main__":
     build()

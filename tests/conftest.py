@@ -10,6 +10,8 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    from paper_2512_15347_amd.build import ensure_built
+    ensure_built()                                   # compiles only when no library has been built yet
 
 
 @pytest.fixture(scope="session")
