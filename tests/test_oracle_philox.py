@@ -20,21 +20,6 @@ def test_generic_rounds_match_numpy_philox4x64():
         assert got == want
 
 
-def test_known_answer_vectors_w32():
-    """The published Philox-4x32-10 vectors (tests/golden/philox4x32_10_kat.txt): pins the 32-bit multipliers,
-    the Weyl increments, the word permutation and the round count of both routines."""
-    import os
-    path = os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_kat.txt")
-    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
-    assert len(rows) == 3
-    for r in rows:
-        w = [int(x, 16) for x in r]
-        ctr, key, want = w[:4], w[4:6], w[6:]
-        assert list(philox.philox4_scalar(ctr, key, W=32)) == want
-        got = philox.philox4x32(np.array([ctr[0]]), ctr[1], ctr[2], ctr[3], key[0], key[1])
-        assert [int(g[0]) for g in got] == want
-
-
 def test_vectorised_matches_generic_w32():
     rng = np.random.default_rng(11)
     c = rng.integers(0, 2**32, size=(64, 4), dtype=np.uint64)
