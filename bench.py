@@ -211,7 +211,7 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=0, help="trajectories in the oracle sample (0 = auto)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("this build runs on ONE GPU: the path has no inter-GPU part (groups are independent and would "
+        sys.exit("this library runs on ONE GPU: the path has no inter-GPU part (groups are independent and would "
                  "shard by prompt); run with --gpus 1")
 
     import numpy as np

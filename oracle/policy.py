@@ -5,7 +5,7 @@ Sec. 5.1 after Eq. 18: with a_t = x_{t+dt} - x_t and s_t = (x_t, t), the per-ste
 r_t = pi_theta(a_t | s_t) / pi_old(a_t | s_t) (Eq. 19), pi being the Gaussian policy induced by the
 Euler-Maruyama step (Eq. 13): N(A_t x_t + B_t u_theta(x_t, t), C_t^2 I).  The objective restricted to
 the K survivors is the mean over survivors and steps of min(r A, clip(r, 1-e, 1+e) A) (Eq. 20, first
-term).  The KL term of Eq. 20 needs a reference policy and is not part of this build.
+term).  The KL term of Eq. 20 needs a reference policy and is not computed here.
 
 Pins: identical weights give ratio 1 and the objective equal to the mean advantage; a constant shift of
 the network output gives a closed-form log-ratio; the clipping cases are checked branch by branch.
