@@ -88,6 +88,10 @@ def stream_kernels_at_stress_shape(pg, torch, n=1024, d=16 * 128 * 128, reps=10)
     res["preview_reward_1024x16x128x128"] = timed(
         lambda: pg.pg_preview_reward(x, u, w, r, n, d, 1.0, -0.7, 0.1, part), 8.0 * n * d)
     res["compact_gather_1024_to_512"] = timed(lambda: pg.pg_compact_gather(x, xo, src, n // 2, d), 8.0 * (n // 2) * d)
+    xb = x.to(torch.bfloat16).view(torch.int16); ub = u.to(torch.bfloat16).view(torch.int16)
+    xob = torch.empty(n, d, dtype=torch.int16, device=dev)
+    res["sde_step_logprob_bf16_storage_1024x16x128x128"] = timed(
+        lambda: pg.pg_sde_step_logprob_bf16(xb, ub, xob, None, None, None, None, ids, n, d, 0.93, -0.1, 0.38, 7, 3, part), 6.0 * n * d)
     res["init_latents_1024x16x128x128"] = timed(lambda: pg.pg_init_latents(xo, ids, 7), 4.0 * n * d)
     # the plain copy above is the practical ceiling for a kernel that reads and writes in equal parts
     res["sde_step_vs_copy_ceiling"] = round(res["sde_step_logprob_1024x16x128x128"]["gbs"] / res["compact_gather_1024_to_512"]["gbs"], 3)

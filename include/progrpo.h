@@ -218,6 +218,16 @@ pg_status pg_sde_step_logprob(const float *x, const float *u, float *x_out, floa
                               const int32_t *orig_id, int64_t n_traj, int64_t d, double A, double B,
                               double C, uint64_t seed, uint32_t step, float *partials, void *stream);
 
+/* pg_sde_step_logprob with the latents and the network output stored as bf16 (6 instead of 12 bytes
+ * per element; a storage variant, not used by the sampling loop): the arithmetic is fp32 on the
+ * bf16 values, x_out is rounded to nearest-even, the noise and the log-prob are those of the fp32
+ * call.  d multiple of 8; rows 16-byte aligned. */
+pg_status pg_sde_step_logprob_bf16(const uint16_t *x, const uint16_t *u, uint16_t *x_out,
+                                   float *logp, float *logp_hist, float *logp_sum,
+                                   const int32_t *src, const int32_t *orig_id, int64_t n_traj,
+                                   int64_t d, double A, double B, double C, uint64_t seed,
+                                   uint32_t step, float *partials, void *stream);
+
 /* rewards[r] = bias + <w, Pc x[r] + Qc u[r]> (Eq. 15-16 with the linear proxy); u may be NULL when
  * Qc == 0.  Same scratch size as pg_step_scratch_floats. */
 pg_status pg_preview_reward(const float *x, const float *u, const float *w, float *rewards,

@@ -86,6 +86,8 @@ _SIGNATURES = {
     "pg_step_scratch_floats": (_i64, [_i64, _i64]),
     "pg_sde_step_logprob": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _f64, _f64, _f64, _u64,
                                     _u32, _vp, _vp]),
+    "pg_sde_step_logprob_bf16": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _f64, _f64, _f64, _u64,
+                                         _u32, _vp, _vp]),
     "pg_preview_reward": (_i32, [_vp, _vp, _vp, _vp, _i64, _i64, _f64, _f64, _f64, _vp, _vp]),
     "pg_ovf_scratch_ints": (_i64, [_i64]),
     "pg_ovf_select": (_i32, [_vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
@@ -347,6 +349,13 @@ def pg_sde_step_logprob(x, u, x_out, logp, logp_hist, logp_sum, src, orig_id, n_
     _check(_lib.pg_sde_step_logprob(_ptr(x), _ptr(u), _ptr(x_out), _ptr(logp), _ptr(logp_hist), _ptr(logp_sum),
                                     _ptr(src), _ptr(orig_id), n_traj, d, A, B, Cc, seed, step, _ptr(partials),
                                     _stream(stream)))
+
+
+def pg_sde_step_logprob_bf16(x, u, x_out, logp, logp_hist, logp_sum, src, orig_id, n_traj, d, A, B, Cc, seed, step,
+                             partials, stream=None):
+    _check(_lib.pg_sde_step_logprob_bf16(_ptr(x), _ptr(u), _ptr(x_out), _ptr(logp), _ptr(logp_hist), _ptr(logp_sum),
+                                         _ptr(src), _ptr(orig_id), n_traj, d, A, B, Cc, seed, step, _ptr(partials),
+                                         _stream(stream)))
 
 
 def pg_preview_reward(x, u, w, rewards, n_traj, d, Pc, Qc, bias, partials, stream=None):

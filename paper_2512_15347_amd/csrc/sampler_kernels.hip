@@ -84,6 +84,50 @@ __global__ __launch_bounds__(STREAM_THREADS) void sde_step_kernel(
   if (threadIdx.x == 0) partials[blockIdx.x] = t;
 }
 
+// The same update with the latents and the network output stored as bf16 (6 instead of 12 bytes per element):
+// arithmetic in fp32, the result rounded to nearest-even.  A lane handles 8 elements per access (two Philox
+// blocks); the noise of an element does not depend on the storage format.
+typedef uint32_t u32x4s __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float bf_lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t w) { return __builtin_bit_cast(float, w & 0xFFFF0000u); }
+__device__ __forceinline__ uint32_t bf_pack(float a, float b) {
+  return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)a) | ((uint32_t)__builtin_bit_cast(uint16_t, (__bf16)b) << 16);
+}
+
+__global__ __launch_bounds__(STREAM_THREADS) void sde_step_bf16_kernel(
+    const uint16_t* __restrict__ x, const uint16_t* __restrict__ u, uint16_t* __restrict__ x_out,
+    const int32_t* __restrict__ src, const int32_t* __restrict__ orig_id, int d8, int chunks, float A, float B,
+    float C, uint32_t k0, uint32_t k1, uint32_t step, float* __restrict__ partials) {
+  const int r = blockIdx.x / chunks, c = blockIdx.x - r * chunks;
+  const int q = src ? src[r] : r;
+  const uint32_t id = (uint32_t)orig_id[r];
+  const u32x4s* xq = reinterpret_cast<const u32x4s*>(x) + (size_t)q * d8;
+  const u32x4s* uq = reinterpret_cast<const u32x4s*>(u) + (size_t)q * d8;
+  u32x4s* xo = reinterpret_cast<u32x4s*>(x_out) + (size_t)r * d8;
+  constexpr int ITERS = STREAM_CHUNK / 8 / STREAM_THREADS;         // 16-byte accesses per lane and chunk
+  float acc = 0.f;
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    const int e8 = c * (STREAM_CHUNK / 8) + it * STREAM_THREADS + threadIdx.x;
+    if (e8 < d8) {
+      const u32x4s xv = __builtin_nontemporal_load(xq + e8);
+      const u32x4s uv = __builtin_nontemporal_load(uq + e8);
+      const f32x4 z0 = philox_normal4((uint32_t)(2 * e8), step, id, STREAM_STEP, k0, k1);
+      const f32x4 z1 = philox_normal4((uint32_t)(2 * e8 + 1), step, id, STREAM_STEP, k0, k1);
+      u32x4s o;
+      o.x = bf_pack(A * bf_lo(xv.x) + B * bf_lo(uv.x) + C * z0.x, A * bf_hi(xv.x) + B * bf_hi(uv.x) + C * z0.y);
+      o.y = bf_pack(A * bf_lo(xv.y) + B * bf_lo(uv.y) + C * z0.z, A * bf_hi(xv.y) + B * bf_hi(uv.y) + C * z0.w);
+      o.z = bf_pack(A * bf_lo(xv.z) + B * bf_lo(uv.z) + C * z1.x, A * bf_hi(xv.z) + B * bf_hi(uv.z) + C * z1.y);
+      o.w = bf_pack(A * bf_lo(xv.w) + B * bf_lo(uv.w) + C * z1.z, A * bf_hi(xv.w) + B * bf_hi(uv.w) + C * z1.w);
+      __builtin_nontemporal_store(o, xo + e8);
+      acc += ((z0.x * z0.x + z0.y * z0.y) + (z0.z * z0.z + z0.w * z0.w)) +
+             ((z1.x * z1.x + z1.y * z1.y) + (z1.z * z1.z + z1.w * z1.w));
+    }
+  }
+  const float t = block_sum_256(acc);
+  if (threadIdx.x == 0) partials[blockIdx.x] = t;
+}
+
 // logp[r] = -1/2 sum_c partial[r, c] - d (ln C + 1/2 ln 2 pi); history and running sum by original id.
 __global__ void logprob_finish_kernel(const float* __restrict__ partials, int chunks, int n_traj,
                                       double log_norm, const int32_t* __restrict__ orig_id,
@@ -309,6 +353,30 @@ extern "C" pg_status pg_sde_step_logprob(const float* x, const float* u, float* 
                                          float* partials, void* stream) {
   return launch_sde_step(x, u, x_out, logp, logp_hist, logp_sum, src, orig_id, n_traj, d, A, B, C, seed, step,
                          partials, nullptr, (hipStream_t)stream);
+}
+
+extern "C" pg_status pg_sde_step_logprob_bf16(const uint16_t* x, const uint16_t* u, uint16_t* x_out, float* logp,
+                                              float* logp_hist, float* logp_sum, const int32_t* src,
+                                              const int32_t* orig_id, int64_t n_traj, int64_t d, double A,
+                                              double B, double C, uint64_t seed, uint32_t step,
+                                              float* partials, void* stream_) {
+  hipStream_t stream = (hipStream_t)stream_;
+  PG_TRY(check_stream_shape(n_traj, d));
+  if (d % 8) return fail(PG_ESHAPE, "pg_sde_step_logprob_bf16: d = %lld must be a multiple of 8", (long long)d);
+  if (n_traj == 0) return PG_OK;
+  if (!x || !u || !x_out || !orig_id || !partials) return fail(PG_EINVAL, "pg_sde_step_logprob_bf16: null pointer");
+  if (x_out == x) return fail(PG_EINVAL, "pg_sde_step_logprob_bf16: x_out must not alias x");
+  if (!(C > 0.0)) return fail(PG_EINVAL, "pg_sde_step_logprob_bf16: noise scale C = %g must be > 0", C);
+  const int chunks = (int)chunks_per_traj(d);
+  sde_step_bf16_kernel<<<dim3((unsigned)(n_traj * chunks)), dim3(STREAM_THREADS), 0, stream>>>(
+      x, u, x_out, src, orig_id, (int)(d / 8), chunks, (float)A, (float)B, (float)C, (uint32_t)seed,
+      (uint32_t)(seed >> 32), step, partials);
+  PG_LAUNCH_CHECK("sde_step_bf16_kernel");
+  const double log_norm = (double)d * (log(C) + 0.5 * log(2.0 * M_PI));
+  logprob_finish_kernel<<<dim3((unsigned)((n_traj + 127) / 128)), dim3(128), 0, stream>>>(
+      partials, chunks, (int)n_traj, log_norm, orig_id, logp, logp_hist, logp_sum);
+  PG_LAUNCH_CHECK("logprob_finish_kernel");
+  return PG_OK;
 }
 
 extern "C" pg_status pg_preview_reward(const float* x, const float* u, const float* w, float* rewards,

@@ -84,6 +84,40 @@ def test_sde_step_with_gather_on_read(lib):
     _step_case(lib, 12, 4096 + 256, seed=9, step=5, A=0.93, B=-0.21, Cc=0.31, src=src)
 
 
+@pytest.mark.parametrize("n,d,gather", [(4, 1024, False), (3, 4096 * 2 + 520, False), (12, 4096 + 256, True)])
+def test_sde_step_bf16_storage_matches_oracle(lib, n, d, gather):
+    """Storage variant: bf16 latents and network output in, bf16 latents out.  The oracle takes the same
+    bf16-representable inputs; the result may differ from the exactly rounded one by the fp32 arithmetic, i.e.
+    by at most one bf16 rounding step; the log-prob is that of the fp32 call."""
+    say(f"sde_step bf16 n={n} d={d}")
+    seed, step, A, B, Cc = 17, 2, 0.93, -0.21, 0.31
+    x, u = workloads.stress_latents(n, d, seed=seed)
+    x = workloads.bf16_round(x); u = workloads.bf16_round(u)
+    src = np.array([0, 2, 3, 7, 8, 11]) if gather else None
+    ids = np.arange(n, dtype=np.int32) * 2 + 5
+    rows = np.arange(n) if src is None else src
+    ids_out = ids[rows]
+    n_out = len(rows)
+    bits = lambda a: torch.from_numpy(workloads.bf16_bits(a).view(np.int16)).to(DEV)
+    xo = torch.zeros(n_out, d, dtype=torch.int16, device=DEV)
+    logp = torch.zeros(n_out, device=DEV)
+    part = torch.zeros(lib.pg_step_scratch_floats(n_out, d), device=DEV)
+    lib.pg_sde_step_logprob_bf16(bits(x), bits(u), xo, logp, None, None, None if src is None else dev(src.astype(np.int32)),
+                                 dev(ids_out.astype(np.int32)), n_out, d, A, B, Cc, seed, step, part)
+    torch.cuda.synchronize()
+    xi = np.stack([philox.normals(seed, philox.STREAM_STEP, int(i), step, d) for i in ids_out])
+    want_x, mean = sampler.sde_step(x[rows].astype(np.float64), u[rows].astype(np.float64), A, B, Cc, xi)
+    got = (xo.cpu().numpy().view(np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    # half a bf16 step is 2^-9 of the value's power of two (<= 2^-8 relative); allow the fp32 arithmetic on top
+    assert np.all(np.abs(got - want_x) <= 2.0 ** -8 * np.abs(want_x) * 1.02 + 1e-30 + 2e-6)
+    exact = workloads.bf16_round(want_x.astype(np.float32)).astype(np.float64)
+    assert np.mean(got == exact) > 0.995                             # rounding decisions differ only near ties
+    np.testing.assert_allclose(logp.cpu().numpy().astype(np.float64), sampler.gaussian_logprob(want_x, mean, Cc), rtol=2e-5)
+    with pytest.raises(lib.PgError):
+        lib.pg_sde_step_logprob_bf16(bits(x), bits(u), xo, logp, None, None, None, dev(ids_out.astype(np.int32)), n_out, 1028, A, B,
+                                     Cc, seed, step, part)
+
+
 def test_sde_step_rejects_bad_arguments(lib):
     x = torch.zeros(2, 64, device=DEV); o = torch.zeros(2, 64, device=DEV)
     ids = torch.zeros(2, dtype=torch.int32, device=DEV); part = torch.zeros(2, device=DEV)
