@@ -183,6 +183,33 @@ def comparison_arms(pg, torch, workloads, cfg, w, inp, seed, inloop_ctx, inloop_
     return out
 
 
+def policy_ratio_pass(pg, torch, cfg, w, inp, seed):
+    """The forward part of the policy update (Eq. 19 and the clipped term of Eq. 20) on a finished run: sampling
+    with the trajectory record kept, then the survivors' T transitions re-evaluated under the same weights.
+    Seconds per group for each; the ratio pass costs T network evaluations of the K survivors."""
+    import time
+    P, T = cfg["P"], cfg["T"]
+    c, keep = pg.make_config(cfg, probe_bias=inp["probe_b"])
+    ctx = pg.pg_create(c)
+    buf = pg.Buffers(ctx, cfg, inputs=inp, weights_flat=pg.pack_weights(ctx, cfg, w), keep_history=True)
+    pg.pg_bind(ctx, buf)
+    M0 = P * cfg["N"]
+    logp_new = torch.zeros(T, M0, device="cuda:0"); ratio = torch.zeros(T, M0, device="cuda:0"); J = torch.zeros(P, device="cuda:0")
+    out = {}
+    for rep in range(2):                                # the second repetition is the timed one
+        torch.cuda.synchronize(); t0 = time.perf_counter()
+        pg.pg_sample_group(ctx, seed)
+        torch.cuda.synchronize(); t1 = time.perf_counter()
+        pg.pg_policy_ratio(ctx, buf.weights, 0.2, logp_new, ratio, J)
+        torch.cuda.synchronize(); t2 = time.perf_counter()
+        out = dict(sampling_with_record_s_per_group=round((t1 - t0) / P, 6), ratio_pass_s_per_group=round((t2 - t1) / P, 6))
+    st = pg.pg_state(ctx, P)
+    out["survivor_steps_per_group_batch"] = st["M"] * T
+    pg.pg_check(ctx)
+    pg.pg_destroy(ctx)
+    return out
+
+
 def recorded_gemm_traffic(workload):
     """HBM bytes per GEMM launch from the committed counter summary, or None when there is none for this
     workload or the kernel source has changed since the counters were taken."""
@@ -296,6 +323,7 @@ def main():
                roofline=roofline, other_kernels=others)
     if not args.no_arms:
         out["comparison_arms"] = comparison_arms(pg, torch, workloads, cfg, w, inp, seed, ctx, buf)
+        out["policy_ratio"] = policy_ratio_pass(pg, torch, cfg, w, inp, seed)
     if not args.no_cpu_baseline:
         budget = args.cpu_sample or {"cfg1": 8, "cfg2": 8}.get(args.workload, 1)
         out["cpu_baseline"] = cpu_baseline(cfg, w, inp, seed, budget)
