@@ -14,9 +14,11 @@ Pins
   Philox-4x64-10), which fixes the round structure, the word permutation, the
   key schedule and the round count.
 * ``philox4x32`` (vectorised, W=32) is compared with ``philox4_scalar(W=32)``.
-* The W=32 multipliers / Weyl increments themselves have no independent check
-  in this environment: **parity unpinned** for those four constants; moment
-  and distribution tests on the resulting normals are the only evidence.
+* The W=32 multipliers / Weyl increments: the two increments have a closed form (fractional parts of
+  the golden ratio and of sqrt(3) - 1, truncated to the word), checked in exact integer arithmetic; all
+  four are compared with the values the GPU vendor's random-number library states in its installed
+  header, and the whole W=32 block function with that library's own generator (a known-answer test that
+  runs where the library can allocate, i.e. next to a GPU).
 * ``normals`` is checked by moments and a Kolmogorov-Smirnov test.
 """
 import numpy as np

@@ -77,3 +77,56 @@ def test_streams_are_distinct_and_keyed_by_original_id():
     assert not np.allclose(a, philox.normals(1, philox.STREAM_INIT, 3, 0, 64))
     assert not np.allclose(a, philox.normals(2, philox.STREAM_STEP, 3, 0, 64))
     np.testing.assert_array_equal(a[:10], philox.normals(1, philox.STREAM_STEP, 3, 0, 10))
+
+
+# ---- the 32-bit constants ----
+def test_weyl_increments_have_their_closed_form():
+    # the key schedule adds the fractional parts of the golden ratio and of sqrt(3) - 1, scaled to the
+    # word width and truncated (SC'11 paper, the paragraph on the Weyl sequence): exact integer arithmetic
+    from math import isqrt
+    for W in (32, 64):
+        c = philox._CONST[W]
+        golden = (isqrt(5 << (2 * W + 8)) - (1 << (W + 4))) >> 5        # floor(2^W (sqrt(5) - 1) / 2)
+        root3 = isqrt(3 << (2 * W)) - (1 << W)                         # floor(2^W (sqrt(3) - 1))
+        assert c["W0"] == golden and c["W1"] == root3
+
+
+def _vendor_philox_constants():
+    """The four 32-bit constants as the GPU vendor's random-number library states them in the header it
+    installs (an independent statement of the generator's published constants)."""
+    import os
+    import re
+    path = "/opt/rocm/include/rocrand/rocrand_philox4x32_10.h"
+    if not os.path.exists(path):
+        return None
+    text = open(path).read()
+    out = {}
+    for ours, theirs in (("M0", "ROCRAND_PHILOX_M4x32_0"), ("M1", "ROCRAND_PHILOX_M4x32_1"),
+                         ("W0", "ROCRAND_PHILOX_W32_0"), ("W1", "ROCRAND_PHILOX_W32_1")):
+        m = re.search(r"#define\s+" + theirs + r"\s+(0[xX][0-9a-fA-F]+)", text)
+        assert m, theirs
+        out[ours] = int(m.group(1), 16)
+    return out
+
+
+def test_w32_constants_match_the_vendor_header():
+    import pytest
+    vendor = _vendor_philox_constants()
+    if vendor is None:
+        pytest.skip("vendor random-number header not installed")
+    assert philox._CONST[32] == vendor
+
+
+def test_kernel_header_states_the_same_constants():
+    # the HIP side keeps its own copy (the two share no code): both must state the published values
+    import os
+    import re
+    import pytest
+    vendor = _vendor_philox_constants()
+    if vendor is None:
+        pytest.skip("vendor random-number header not installed")
+    here = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    text = open(os.path.join(here, "paper_2512_15347_amd", "csrc", "philox.hpp")).read()
+    for name in ("M0", "M1", "W0", "W1"):
+        m = re.search(r"PHILOX_" + name + r"\s*=\s*(0[xX][0-9a-fA-F]+)", text)
+        assert m and int(m.group(1), 16) == vendor[name]
