@@ -9,6 +9,11 @@
  *  - Calls return asynchronously (work queued on the stream) unless stated otherwise.
  *  - Every call returns a pg_status.  Argument errors are found on the host before any launch.
  *    pg_last_error() gives a human-readable message for the last failure on this thread.
+ *  - Errors that only the device can see (a non-finite proxy reward, a bad count met by a selection
+ *    kernel) cannot come back from an asynchronous call: they set a sticky word in pg_buffers.status, the
+ *    kernels keep every index they write in bounds, and pg_check() reports them.  CALL pg_check AFTER
+ *    pg_sample_group (or after the last call of a hand-written loop) BEFORE USING THE RESULTS: after a
+ *    non-finite reward the survivor sets are the first k slots of each group, not Eq. 10's.
  *  - Packed batch layout: the M active trajectories are rows of x[M, d] (fp32, d = C*H*W, NCHW
  *    inside a row), ordered by (group, ascending original slot); group g owns rows
  *    group_offsets[g] .. group_offsets[g+1]-1.  orig_id[row] = g*N + original slot.
@@ -110,7 +115,8 @@ typedef struct pg_buffers {
   const uint16_t *ctx;     /* bf16 [P, Lc, Dc]; NULL if Lc == 0 */
   const float *y;          /* [P, D] prompt vector added to the timestep embedding */
   int32_t *status;         /* [4] device words: [0] = sticky error bits (1 = non-finite reward, 2 = bad k) */
-  void *workspace;         /* pg_workspace_bytes() bytes, 256-byte aligned */
+  void *workspace;         /* pg_workspace_bytes() bytes, 256-byte aligned; the library's from pg_bind (which writes
+                              the schedule's tables into it) to the next pg_bind / pg_destroy: do not write it */
   size_t workspace_bytes;
   float *x_hist;           /* optional (NULL: not kept) [T+1, M0, d] latents by ORIGINAL id: slice 0 = x_0,
                               slice s+1 = state after step s (rows of trajectories pruned before step s are not written) */
@@ -139,6 +145,12 @@ pg_status pg_weight_slot(const pg_ctx *ctx, int32_t id, int32_t block, int64_t *
 pg_status pg_get_tables(const pg_ctx *ctx, double *A, double *B, double *C, double *P, double *Q,
                         double *t_in);
 
+/* The funnel of Sec. 5.2 as the library will follow it: for a prune at `step`, the number of trajectories
+ * each group keeps (k: [host] P ints; a group without an entry at this step keeps what it has) and their
+ * exclusive scan (offsets: [host] P+1 ints), given that every earlier checkpoint was followed.  Either may be
+ * NULL.  These rows are what pg_bind places in the workspace, so that a prune uploads nothing. */
+pg_status pg_get_schedule(const pg_ctx *ctx, int32_t step, int32_t *k, int32_t *offsets);
+
 pg_status pg_bind(pg_ctx *ctx, const pg_buffers *buf);
 
 /* Host-side view of the loop state: active trajectories M, index of the current x buffer and of
@@ -151,7 +163,9 @@ pg_status pg_state(const pg_ctx *ctx, int32_t *M, int32_t *cur_x, int32_t *cur_i
  * by (seed, original id); resets offsets, ids, log-prob records, counters. */
 pg_status pg_init_group(pg_ctx *ctx, uint64_t seed, void *stream);
 
-/* u = network(x, t_s, prompt) on every active trajectory (the drift input of Eq. 12). */
+/* u = network(x, t_s, prompt) on every active trajectory (the drift input of Eq. 12).  Steps come in order:
+ * `step` must be the number of pg_step calls since pg_init_group (PG_ESCHED otherwise; the same holds for
+ * pg_prune, pg_prune_forced and pg_step). */
 pg_status pg_net_forward(pg_ctx *ctx, int32_t step, void *stream);
 
 /* Checkpoint of Sec. 5.1 "Dynamic latent feature-based pruning": preview (Eq. 14-15), proxy reward
@@ -167,10 +181,11 @@ pg_status pg_prune_forced(pg_ctx *ctx, int32_t step, const uint64_t *masks, uint
                           void *stream);
 
 /* Euler-Maruyama update (Eq. 13) of every active trajectory with Philox noise keyed by
- * (seed, original id, step), plus the Gaussian log-prob of the step (policy of Eq. 19). */
+ * (seed, original id, step), plus the Gaussian log-prob of the step (policy of Eq. 19).  PG_ESCHED if the
+ * schedule prunes a group at this step and that prune has not been made (Sec. 5.2: the funnel is followed). */
 pg_status pg_step(pg_ctx *ctx, int32_t step, void *stream);
 
-/* Final rewards of the survivors and their group-normalised advantages (Eq. 18). */
+/* Final rewards of the survivors and their group-normalised advantages (Eq. 18); after all T steps. */
 pg_status pg_advantages(pg_ctx *ctx, void *stream);
 
 /* The whole loop: init, T x (network, prune at checkpoints, step), advantages. */
@@ -188,7 +203,9 @@ pg_status pg_select_final(pg_ctx *ctx, int32_t mode, const int32_t *k_per_group,
 /* Forward part of the policy update on the survivors (Sec. 5.1, Eq. 19 and the first term of Eq. 20): the
  * stored transitions (x_s, x_{s+1}) of every surviving trajectory are re-evaluated under another weight set
  * (`weights_new`, [device], same layout as pg_buffers.weights): logp_new[s, id] = log N(x_{s+1}; A_s x_s +
- * B_s u_new(x_s, t_s), C_s^2 I), ratio[s, id] = exp(logp_new - logp_hist), and per group
+ * B_s u_new(x_s, t_s), C_s^2 I), ratio[s, id] = exp(log pi_new - log pi_old) with the exponent summed in its
+ * per-element terms (the noise the sampler drew against the noise the new policy would need, so nothing
+ * cancels between two large log-probs), and per group
  * J[g] = mean over survivors and steps of min(r A, clip(r, 1 - clip_eps, 1 + clip_eps) A) with the advantages of
  * pg_advantages.  logp_new, ratio: [device] [T, M0] by original id (NaN off the survivors); J: [device] [P].
  * Needs pg_buffers.x_hist, a finished loop (all T steps and pg_advantages) and a network.  Overwrites the
@@ -305,6 +322,14 @@ pg_status pg_attention_bf16(const uint16_t *q, const uint16_t *k, const uint16_t
 pg_status pg_profile_begin(int32_t max_records);
 pg_status pg_profile_read(int32_t kind, double *total_ms, double *total_work, int64_t *launches);
 pg_status pg_profile_end(void);
+
+
+/* Launches `blocks` workgroups of 256 lanes that each issue iters x 8 bf16 32x32x16 MFMAs per wave on registers
+ * alone (no LDS, no memory traffic but one float per lane written to out, [device] blocks * 256 floats): the rate
+ * the matrix pipes sustain on this part, the yardstick beside the published peak.  operand_scale 0 gives all-zero
+ * operands, 1 gives values spread over [-1, 1].  *flops (nullable, [host]) receives the MFMA flop count. */
+pg_status pg_mfma_probe(int32_t blocks, int32_t iters, float operand_scale, float *out, double *flops,
+                        void *stream);
 
 #ifdef __cplusplus
 }

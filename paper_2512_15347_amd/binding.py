@@ -70,6 +70,7 @@ _SIGNATURES = {
     "pg_weights_numel": (_i64, [_vp]),
     "pg_weight_slot": (_i32, [_vp, _i32, _i32, C.POINTER(_i64), _ip, _ip, _ip]),
     "pg_get_tables": (_i32, [_vp, _dp, _dp, _dp, _dp, _dp, _dp]),
+    "pg_get_schedule": (_i32, [_vp, _i32, _ip, _ip]),
     "pg_bind": (_i32, [_vp, C.POINTER(pg_buffers)]),
     "pg_state": (_i32, [_vp, _ip, _ip, _ip, _ip, C.POINTER(_i64), C.POINTER(_i64)]),
     "pg_init_group": (_i32, [_vp, _u64, _vp]),
@@ -98,6 +99,7 @@ _SIGNATURES = {
     "pg_group_advantages": (_i32, [_vp, _vp, _i32, _f64, _vp, _vp]),
     "pg_gemm_bf16": (_i32, [_vp, _i64, _vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _vp]),
     "pg_attention_bf16": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _vp]),
+    "pg_mfma_probe": (_i32, [_i32, _i32, C.c_float, _vp, _dp, _vp]),
     "pg_profile_begin": (_i32, [_i32]),
     "pg_profile_read": (_i32, [_i32, _dp, _dp, C.POINTER(_i64)]),
     "pg_profile_end": (_i32, []),
@@ -203,6 +205,12 @@ def pg_get_tables(ctx, T):
     arrs = [(C.c_double * T)() for _ in range(6)]
     _check(_lib.pg_get_tables(ctx, *arrs))
     return {k: np.array(a[:]) for k, a in zip(("A", "B", "C", "P", "Q", "t_in"), arrs)}
+
+
+def pg_get_schedule(ctx, step, P):
+    k, off = (C.c_int32 * P)(), (C.c_int32 * (P + 1))()
+    _check(_lib.pg_get_schedule(ctx, step, k, off))
+    return list(k), list(off)
 
 
 def pack_weights(ctx, cfg, weights):
@@ -402,6 +410,12 @@ def pg_gemm_bf16(A, lda, W, ldw, bias, Cout, ldc, M, N, K, stream=None):
 
 def pg_attention_bf16(q, k, vt, out, B, Lq, Lk, heads, hd, stream=None):
     _check(_lib.pg_attention_bf16(_ptr(q), _ptr(k), _ptr(vt), _ptr(out), B, Lq, Lk, heads, hd, _stream(stream)))
+
+
+def pg_mfma_probe(blocks, iters, operand_scale, out, stream=None):
+    flops = C.c_double()
+    _check(_lib.pg_mfma_probe(blocks, iters, operand_scale, _ptr(out), C.byref(flops), _stream(stream)))
+    return flops.value
 
 
 def pg_profile_begin(max_records=1 << 16):

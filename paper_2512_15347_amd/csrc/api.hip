@@ -186,10 +186,13 @@ static pg_status validate(const pg_config& f) {
 static pg_status plan_workspace(pg_ctx* c) {
   size_t off = 0;
   auto take = [&](size_t bytes) { const size_t o = off; off = align256(off + bytes); return o; };
-  c->ws_partials = take(sizeof(float) * (size_t)c->M0 * chunks_per_traj(c->d));
+  c->ws_partials = take(2 * sizeof(float) * (size_t)c->M0 * chunks_per_traj(c->d));   // two sums per workgroup at most
   c->ws_k = take(sizeof(int32_t) * c->cfg.P);
   c->ws_newoff = take(sizeof(int32_t) * (c->cfg.P + 1));
   c->ws_forced = take(sizeof(uint64_t) * c->cfg.P + sizeof(int32_t) * c->M0);   // masks + sel of the OVF shadow run
+  c->ws_sched = take(sizeof(int32_t) * c->sched_table.size());                  // the funnel, uploaded by pg_bind
+  c->ws_off0 = take(sizeof(int32_t) * (c->cfg.P + 1));                          // offsets of the full groups
+  c->ws_logr = take(sizeof(double) * (size_t)c->cfg.T * c->M0);                 // fp64 log-ratios of pg_policy_ratio
   c->ws_net = off;
   PG_TRY(net_plan(c));
   c->ws_total = align256(off + c->net.total);
@@ -287,6 +290,22 @@ extern "C" pg_status pg_create(const pg_config* cfg, pg_ctx** out) {
       prev_s = e.first; prev_k = e.second;
     }
   }
+  // the funnel when every prune follows the schedule: row s = counts kept at step s | their exclusive scan
+  {
+    const int P = f.P, row = 2 * P + 1;
+    c->sched_table.assign((size_t)T * row, 0);
+    std::vector<int> size(P, f.N);
+    for (int s = 0; s < T; ++s) {
+      int32_t* k = c->sched_table.data() + (size_t)s * row;
+      int32_t* off = k + P;
+      for (int g = 0; g < P; ++g) {
+        k[g] = size[g];
+        for (auto& e : c->sched[g]) if (e.first == s) k[g] = e.second;
+        off[g + 1] = off[g] + k[g];
+        size[g] = k[g];
+      }
+    }
+  }
   // nullify host pointers we must not keep
   c->cfg.tab_A = c->cfg.tab_B = c->cfg.tab_C = c->cfg.tab_P = c->cfg.tab_Q = c->cfg.tab_tin = nullptr;
   c->cfg.sched_group = c->cfg.sched_step = c->cfg.sched_k = nullptr;
@@ -301,6 +320,7 @@ extern "C" pg_status pg_create(const pg_config* cfg, pg_ctx** out) {
 extern "C" void pg_destroy(pg_ctx* c) {
   if (!c) return;
   if (c->staging) (void)hipHostFree(c->staging);
+  if (c->staging_read) (void)hipEventDestroy(c->staging_read);
   delete c;
 }
 
@@ -337,6 +357,16 @@ extern "C" pg_status pg_get_tables(const pg_ctx* c, double* A, double* B, double
   return PG_OK;
 }
 
+extern "C" pg_status pg_get_schedule(const pg_ctx* c, int32_t step, int32_t* k, int32_t* offsets) {
+  if (!c) return fail(PG_EINVAL, "pg_get_schedule: null context");
+  if (step < 0 || step >= c->cfg.T) return fail(PG_EINVAL, "step %d out of range", step);
+  const int P = c->cfg.P;
+  const int32_t* row = c->sched_table.data() + (size_t)step * (2 * P + 1);
+  if (k) memcpy(k, row, sizeof(int32_t) * P);
+  if (offsets) memcpy(offsets, row + P, sizeof(int32_t) * (P + 1));
+  return PG_OK;
+}
+
 extern "C" pg_status pg_bind(pg_ctx* c, const pg_buffers* b) {
   if (!c || !b) return fail(PG_EINVAL, "pg_bind: null argument");
   c->bound = false;
@@ -354,10 +384,18 @@ extern "C" pg_status pg_bind(pg_ctx* c, const pg_buffers* b) {
       ((uintptr_t)b->ctx & 15))
     return fail(PG_ESHAPE, "pg_bind: buffers must be 16-byte aligned (workspace 256)");
   if (!c->staging) {
-    const size_t n = (size_t)(c->cfg.T + 2) * (2 * c->cfg.P + 2);   // one slot per step, one for init, one for the final selection
-    PG_HIP(hipHostMalloc((void**)&c->staging, n * sizeof(int32_t), hipHostMallocDefault));
+    PG_HIP(hipHostMalloc((void**)&c->staging, (size_t)(2 * c->cfg.P + 1) * sizeof(int32_t), hipHostMallocDefault));
+    PG_HIP(hipEventCreateWithFlags(&c->staging_read, hipEventDisableTiming));
   }
   c->buf = *b;
+  // the schedule's counts and offsets live in the workspace from here on (synchronous copies: pg_bind is set-up)
+  {
+    std::vector<int32_t> off0(c->cfg.P + 1);
+    for (int g = 0; g <= c->cfg.P; ++g) off0[g] = g * c->cfg.N;
+    PG_HIP(hipMemcpy((char*)b->workspace + c->ws_sched, c->sched_table.data(), sizeof(int32_t) * c->sched_table.size(),
+                     hipMemcpyHostToDevice));
+    PG_HIP(hipMemcpy((char*)b->workspace + c->ws_off0, off0.data(), sizeof(int32_t) * off0.size(), hipMemcpyHostToDevice));
+  }
   c->bound = true;
   c->initialised = false;
   c->context_ready = false;
@@ -386,9 +424,8 @@ extern "C" pg_status pg_init_group(pg_ctx* c, uint64_t seed, void* stream) {
   c->M = c->M0; c->cur_x = 0; c->cur_id = 0;
   c->pending_gather = false; c->net_fresh = false;
   c->evals = 0; c->updates = 0; c->steps_done = 0; c->advantages_done = false;
-  int32_t* slot = c->staging + (size_t)f.T * (2 * f.P + 2);
-  for (int g = 0; g <= f.P; ++g) { c->offsets[g] = g * f.N; slot[g] = g * f.N; }
-  PG_HIP(hipMemcpyAsync(c->buf.group_offsets, slot, sizeof(int32_t) * (f.P + 1), hipMemcpyHostToDevice, s));
+  for (int g = 0; g <= f.P; ++g) c->offsets[g] = g * f.N;
+  PG_HIP(hipMemcpyAsync(c->buf.group_offsets, ws(c, c->ws_off0), sizeof(int32_t) * (f.P + 1), hipMemcpyDeviceToDevice, s));
   PG_TRY(launch_iota(c->buf.orig_id[0], c->M0, s));
   PG_TRY(launch_fill_group_of(c->buf.group_offsets, f.P, c->buf.group_of, s));
   PG_TRY(launch_fill_u32(c->buf.logp_hist, 0x7FC00000u, (size_t)f.T * c->M0, s));
@@ -408,6 +445,7 @@ extern "C" pg_status pg_init_group(pg_ctx* c, uint64_t seed, void* stream) {
 extern "C" pg_status pg_net_forward(pg_ctx* c, int32_t step, void* stream) {
   if (!c || !c->bound || !c->initialised) return fail(PG_ESCHED, "pg_net_forward: call pg_init_group first");
   if (step < 0 || step >= c->cfg.T) return fail(PG_EINVAL, "step %d out of range", step);
+  if (step != c->steps_done) return fail(PG_ESCHED, "pg_net_forward: step %d out of order (next is %d)", step, c->steps_done);
   if (c->pending_gather) return fail(PG_ESCHED, "pg_net_forward: a prune is waiting for its pg_step");
   if (c->cfg.net_kind != PG_NET_NONE)
     PG_TRY(net_forward(c, step, c->buf.x[c->cur_x], c->buf.weights, (hipStream_t)stream));
@@ -416,14 +454,13 @@ extern "C" pg_status pg_net_forward(pg_ctx* c, int32_t step, void* stream) {
   return PG_OK;
 }
 
-// shared tail of pg_prune / pg_prune_forced once sel_idx and the new offsets are on the device
-static pg_status finish_prune(pg_ctx* c, const std::vector<int>& new_off, hipStream_t s) {
+// shared tail of pg_prune / pg_prune_forced once sel_idx is on the device; new_off_dev: the new offsets [device]
+static pg_status finish_prune(pg_ctx* c, const std::vector<int>& new_off, const int32_t* new_off_dev, hipStream_t s) {
   const int P = c->cfg.P;
   const int M_new = new_off[P];
   PG_TRY(launch_gather_ids(c->buf.orig_id[c->cur_id], c->buf.sel_idx, M_new, c->buf.orig_id[1 - c->cur_id], s));
   c->cur_id = 1 - c->cur_id;
-  PG_HIP(hipMemcpyAsync(c->buf.group_offsets, ws(c, c->ws_newoff), sizeof(int32_t) * (P + 1),
-                        hipMemcpyDeviceToDevice, s));
+  PG_HIP(hipMemcpyAsync(c->buf.group_offsets, new_off_dev, sizeof(int32_t) * (P + 1), hipMemcpyDeviceToDevice, s));
   PG_TRY(launch_fill_group_of(c->buf.group_offsets, P, c->buf.group_of, s));
   c->offsets = new_off;
   c->M = M_new;
@@ -436,6 +473,7 @@ static pg_status prune_common(pg_ctx* c, int step, const uint64_t* forced, uint6
   if (!c || !c->bound || !c->initialised) return fail(PG_ESCHED, "pg_prune: call pg_init_group first");
   const pg_config& f = c->cfg;
   if (step < 0 || step >= f.T) return fail(PG_EINVAL, "step %d out of range", step);
+  if (step != c->steps_done) return fail(PG_ESCHED, "pg_prune: step %d out of order (next is %d)", step, c->steps_done);
   if (!c->net_fresh) return fail(PG_ESCHED, "pg_prune: no network evaluation for the current latents");
   if (c->pending_gather) return fail(PG_ESCHED, "pg_prune: previous prune not yet consumed by pg_step");
   const int P = f.P;
@@ -452,23 +490,32 @@ static pg_status prune_common(pg_ctx* c, int step, const uint64_t* forced, uint6
   }
   if (!any && !forced) return fail(PG_ESCHED, "step %d is not a checkpoint of any group", step);
   for (int g = 0; g < P; ++g) new_off[g + 1] = new_off[g] + k[g];
-  int32_t* slot = c->staging + (size_t)step * (2 * P + 2);
-  memcpy(slot, k.data(), sizeof(int32_t) * P);
-  memcpy(slot + P, new_off.data(), sizeof(int32_t) * (P + 1));
-  PG_HIP(hipMemcpyAsync(ws(c, c->ws_k), slot, sizeof(int32_t) * P, hipMemcpyHostToDevice, s));
-  PG_HIP(hipMemcpyAsync(ws(c, c->ws_newoff), slot + P, sizeof(int32_t) * (P + 1), hipMemcpyHostToDevice, s));
+  // Counts and new offsets on the device: the row of the funnel table that pg_bind uploaded, whenever the group
+  // sizes are those of the schedule (always, unless a forced prune has departed from it).  Otherwise, and only
+  // then, they go up synchronously.
+  const int32_t* row = c->sched_table.data() + (size_t)step * (2 * P + 1);
+  const bool on_schedule = std::equal(k.begin(), k.end(), row) && std::equal(new_off.begin(), new_off.end(), row + P);
+  const int32_t* k_dev = (const int32_t*)ws(c, c->ws_sched) + (size_t)step * (2 * P + 1);
+  const int32_t* off_dev = k_dev + P;
+  if (!on_schedule) {
+    PG_HIP(hipStreamSynchronize(s));
+    PG_HIP(hipMemcpy(ws(c, c->ws_k), k.data(), sizeof(int32_t) * P, hipMemcpyHostToDevice));
+    PG_HIP(hipMemcpy(ws(c, c->ws_newoff), new_off.data(), sizeof(int32_t) * (P + 1), hipMemcpyHostToDevice));
+    k_dev = (const int32_t*)ws(c, c->ws_k);
+    off_dev = (const int32_t*)ws(c, c->ws_newoff);
+  }
   PG_TRY(pg_preview_reward(c->buf.x[c->cur_x], c->buf.u, c->buf.probe_w, c->buf.rewards, c->M, c->d,
                            c->Pv[step], c->Qv[step], f.probe_bias, (float*)ws(c, c->ws_partials), s));
   if (!forced) {
-    PG_TRY(launch_ovf(c->buf.rewards, c->buf.group_offsets, (int32_t*)ws(c, c->ws_k), P,
-                      (int32_t*)ws(c, c->ws_newoff), c->buf.masks, c->buf.sel_idx, c->buf.status, s));
-    return finish_prune(c, new_off, s);
+    PG_TRY(launch_ovf(c->buf.rewards, c->buf.group_offsets, k_dev, P, off_dev, c->buf.masks, c->buf.sel_idx,
+                      c->buf.status, s));
+    return finish_prune(c, new_off, off_dev, s);
   }
   // forced survivors: run the OVF into shadow buffers (for the record), then impose the masks
   uint64_t* shadow_masks = (uint64_t*)ws(c, c->ws_forced);
   int32_t* shadow_sel = (int32_t*)(ws(c, c->ws_forced) + sizeof(uint64_t) * P);
-  PG_TRY(launch_ovf(c->buf.rewards, c->buf.group_offsets, (int32_t*)ws(c, c->ws_k), P,
-                    (int32_t*)ws(c, c->ws_newoff), shadow_masks, shadow_sel, c->buf.status, s));
+  PG_TRY(launch_ovf(c->buf.rewards, c->buf.group_offsets, k_dev, P, off_dev, shadow_masks, shadow_sel,
+                    c->buf.status, s));
   if (ovf_masks_out)
     PG_HIP(hipMemcpyAsync(ovf_masks_out, shadow_masks, sizeof(uint64_t) * P, hipMemcpyDeviceToDevice, s));
   for (int g = 0; g < P; ++g) {
@@ -484,7 +531,7 @@ static pg_status prune_common(pg_ctx* c, int step, const uint64_t* forced, uint6
   PG_HIP(hipMemcpy(ws(c, c->ws_newoff), new_off.data(), sizeof(int32_t) * (P + 1), hipMemcpyHostToDevice));
   PG_TRY(launch_masks_to_sel(c->buf.masks, c->buf.group_offsets, (int32_t*)ws(c, c->ws_newoff), P,
                              c->buf.sel_idx, s));
-  return finish_prune(c, new_off, s);
+  return finish_prune(c, new_off, (const int32_t*)ws(c, c->ws_newoff), s);
 }
 
 extern "C" pg_status pg_prune(pg_ctx* c, int32_t step, void* stream) {
@@ -502,6 +549,13 @@ extern "C" pg_status pg_step(pg_ctx* c, int32_t step, void* stream) {
   if (step < 0 || step >= c->cfg.T) return fail(PG_EINVAL, "step %d out of range", step);
   if (!c->net_fresh) return fail(PG_ESCHED, "pg_step: no network evaluation for the current latents");
   if (step != c->steps_done) return fail(PG_ESCHED, "pg_step: step %d out of order (next is %d)", step, c->steps_done);
+  if (c->is_checkpoint[step] && !c->pending_gather) {
+    // a group whose schedule has an entry here and that still holds more than that entry keeps must be pruned first
+    for (int g = 0; g < c->cfg.P; ++g)
+      for (auto& e : c->sched[g])
+        if (e.first == step && c->offsets[g + 1] - c->offsets[g] > e.second)
+          return fail(PG_ESCHED, "pg_step: step %d is a checkpoint of group %d; call pg_prune first", step, g);
+  }
   float* hist_next = c->buf.x_hist ? c->buf.x_hist + (size_t)(step + 1) * c->M0 * c->d : nullptr;
   PG_TRY(launch_sde_step(c->buf.x[c->cur_x], c->buf.u, c->buf.x[1 - c->cur_x], nullptr,
                          c->buf.logp_hist + (size_t)step * c->M0, c->buf.logp_sum,
@@ -519,6 +573,8 @@ extern "C" pg_status pg_step(pg_ctx* c, int32_t step, void* stream) {
 extern "C" pg_status pg_advantages(pg_ctx* c, void* stream) {
   if (!c || !c->bound || !c->initialised) return fail(PG_ESCHED, "pg_advantages: call pg_init_group first");
   if (c->pending_gather) return fail(PG_ESCHED, "pg_advantages: a prune is waiting for its pg_step");
+  if (c->steps_done != c->cfg.T)
+    return fail(PG_ESCHED, "pg_advantages: %d of %d steps taken (Eq. 18 is on the final latents)", c->steps_done, c->cfg.T);
   PG_TRY(pg_preview_reward(c->buf.x[c->cur_x], nullptr, c->buf.probe_w, c->buf.rewards, c->M, c->d, 1.0, 0.0,
                            c->cfg.probe_bias, (float*)ws(c, c->ws_partials), stream));
   PG_TRY(pg_group_advantages(c->buf.rewards, c->buf.group_offsets, c->cfg.P, c->cfg.adv_eps, c->buf.adv, stream));
@@ -543,11 +599,16 @@ extern "C" pg_status pg_select_final(pg_ctx* c, int32_t mode, const int32_t* k_p
       return fail(PG_EINVAL, "pg_select_final: k = %d for group %d of %d trajectories", k_per_group[g], g, n);
     new_off[g + 1] = new_off[g] + k_per_group[g];
   }
-  int32_t* slot = c->staging + (size_t)(c->cfg.T + 1) * (2 * P + 2);
+  // the counts go up through the pinned slot; a copy of an earlier call that is still queued must have read
+  // the slot before it is written again
+  if (c->staging_in_flight) PG_HIP(hipEventSynchronize(c->staging_read));
+  int32_t* slot = c->staging;
   memcpy(slot, k_per_group, sizeof(int32_t) * P);
   memcpy(slot + P, new_off.data(), sizeof(int32_t) * (P + 1));
   PG_HIP(hipMemcpyAsync(ws(c, c->ws_k), slot, sizeof(int32_t) * P, hipMemcpyHostToDevice, s));
   PG_HIP(hipMemcpyAsync(ws(c, c->ws_newoff), slot + P, sizeof(int32_t) * (P + 1), hipMemcpyHostToDevice, s));
+  PG_HIP(hipEventRecord(c->staging_read, s));
+  c->staging_in_flight = true;
   if (mode == 0)
     PG_TRY(launch_ovf(c->buf.rewards, c->buf.group_offsets, (int32_t*)ws(c, c->ws_k), P,
                       (int32_t*)ws(c, c->ws_newoff), c->buf.masks, c->buf.sel_idx, c->buf.status, s));
@@ -595,10 +656,11 @@ extern "C" pg_status pg_policy_ratio(pg_ctx* c, const uint16_t* weights_new, dou
     PG_TRY(pg_compact_gather(c->buf.x_hist + (size_t)t * slice, xb, ids, c->M, c->d, stream));
     PG_TRY(net_forward(c, t, xb, weights_new, s));
     PG_TRY(launch_transition_logprob(xb, c->buf.u, c->buf.x_hist + (size_t)(t + 1) * slice, ids, c->M, c->d, c->A[t],
-                                     c->B[t], c->C[t], logp_new + (size_t)t * c->M0, (float*)ws(c, c->ws_partials), s));
+                                     c->B[t], c->C[t], c->seed, (uint32_t)t, logp_new + (size_t)t * c->M0,
+                                     (double*)ws(c, c->ws_logr) + (size_t)t * c->M0, (float*)ws(c, c->ws_partials), s));
   }
   c->net_fresh = false;
-  return launch_surrogate(logp_new, c->buf.logp_hist, c->buf.adv, c->buf.group_offsets, ids, f.P, f.T, c->M0,
+  return launch_surrogate((const double*)ws(c, c->ws_logr), c->buf.adv, c->buf.group_offsets, ids, f.P, f.T, c->M0,
                           clip_eps, ratio, J, s);
 }
 

@@ -20,7 +20,8 @@ struct pg_ctx {
   std::vector<WeightSlot> top;            // PG_W_COUNT entries (per-block ones hold block-0 offsets)
   int64_t block_stride = 0, weights_numel = 0;
   // workspace plan
-  size_t ws_partials = 0, ws_k = 0, ws_newoff = 0, ws_forced = 0, ws_net = 0, ws_total = 0;
+  size_t ws_partials = 0, ws_k = 0, ws_newoff = 0, ws_forced = 0, ws_sched = 0, ws_off0 = 0, ws_logr = 0, ws_net = 0,
+         ws_total = 0;
   NetPlan net{};
   // bound buffers
   pg_buffers buf{};
@@ -34,8 +35,14 @@ struct pg_ctx {
   int steps_done = 0;                     // steps taken since pg_init_group
   bool advantages_done = false;
   bool context_ready = false;             // step-independent network precomputation done
-  // pinned host staging for the per-checkpoint k / offsets uploads: [T][2P+2] ints
+  // The funnel as the schedule fixes it: row s = k[P] | new_offsets[P+1] of a prune at step s when every earlier
+  // prune followed the schedule.  Uploaded into the workspace once (pg_bind), so a prune needs no host -> device copy.
+  std::vector<int32_t> sched_table;       // [T][2P+1]
+  // pinned host slot for the counts pg_select_final takes per call (2P+1 ints), and the event that tells when the
+  // copy out of it has run (the host waits on it before writing the slot again)
   int32_t* staging = nullptr;
+  hipEvent_t staging_read = nullptr;
+  bool staging_in_flight = false;
 };
 
 namespace pg {
@@ -51,8 +58,9 @@ pg_status launch_sde_step(const float* x, const float* u, float* x_out, float* l
                           float* hist_next, hipStream_t s);
 pg_status launch_transition_logprob(const float* x, const float* u, const float* x_next_by_id,
                                     const int32_t* orig_id, int64_t n_traj, int64_t d, double A, double B, double C,
-                                    float* logp_by_id, float* partials, hipStream_t s);
-pg_status launch_surrogate(const float* logp_new, const float* logp_old, const float* adv, const int32_t* offsets,
+                                    uint64_t seed, uint32_t step, float* logp_by_id, double* log_ratio_by_id,
+                                    float* partials, hipStream_t s);
+pg_status launch_surrogate(const double* log_ratio, const float* adv, const int32_t* offsets,
                            const int32_t* orig_id, int n_groups, int T, int M0, double clip_eps, float* ratio,
                            float* J, hipStream_t s);
 // small launches (ovf_kernels.hip)

@@ -36,7 +36,10 @@ __device__ __forceinline__ int lds_off(int row, int chunk) { return (row * CH + 
 // 16 bytes per lane straight from global memory into LDS (no register staging): the wave writes the
 // 1 KB starting at LDS address `lds_addr` (wave-uniform), lane l at +16 l.  Issued through inline
 // assembly so that the operand reads of the other LDS stage are not made to wait for it; completion
-// is awaited explicitly (wait_dma) before the barrier that publishes the stage.
+// is awaited explicitly (wait_dma) before the barrier that publishes the stage.  The statement overwrites m0
+// without naming it as clobbered: m0 is a reserved register for this compiler (it refuses it in a clobber list
+// and writes m0 itself directly before each instruction of its own that reads it), so no value of the
+// surrounding code lives in m0 across the statement.
 __device__ __forceinline__ void dma16(const uint16_t* g, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_addr) : "memory");
 }
@@ -51,30 +54,15 @@ __device__ __forceinline__ void wait_dma() {
 // with the non-temporal hint so that the operand panels shared by the tiles of an XCD stay resident.
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
-#ifndef PG_GEMM_STREAM
-#define PG_GEMM_STREAM 1
-#endif
 __device__ __forceinline__ void store_stream(float* p, const float4 v) {
-#if PG_GEMM_STREAM
   __builtin_nontemporal_store(f32x4v{v.x, v.y, v.z, v.w}, reinterpret_cast<f32x4v*>(p));
-#else
-  *reinterpret_cast<float4*>(p) = v;
-#endif
 }
 __device__ __forceinline__ void store_stream(uint16_t* p, const uint2 v) {
-#if PG_GEMM_STREAM
   __builtin_nontemporal_store(u32x2v{v.x, v.y}, reinterpret_cast<u32x2v*>(p));
-#else
-  *reinterpret_cast<uint2*>(p) = v;
-#endif
 }
 __device__ __forceinline__ float4 load_stream(const float* p) {
-#if PG_GEMM_STREAM
   const f32x4v v = __builtin_nontemporal_load(reinterpret_cast<const f32x4v*>(p));
   return float4{v[0], v[1], v[2], v[3]};
-#else
-  return *reinterpret_cast<const float4*>(p);
-#endif
 }
 
 // gelu_tanh(x) = x/2 (1 + tanh(y)) = x / (1 + exp(-2y)),  y = sqrt(2/pi) (x + 0.044715 x^3);
@@ -462,10 +450,8 @@ static pg_status launch_tile(const GemmArgs& a, hipStream_t s) {
 // Tile choice.  A launch runs in rounds of 256 concurrent workgroups (one per compute unit); the last
 // round is usually part empty, and with few K steps a tile's fixed prologue / epilogue weighs more.
 // Pick the shape with the best product of slot occupancy and the measured relative speed of its main
-// loop.  PROGRPO_GEMM_TILE (0..5) overrides the heuristic; it is a tuning aid.
+// loop.
 static int pick_tile(const GemmArgs& a, int epilogue) {
-  static const int forced = [] { const char* e = getenv("PROGRPO_GEMM_TILE"); return e ? atoi(e) : -1; }();
-  if (forced >= 0 && forced <= 5) return forced;
   // columns written row-major / produced through swapped operand roles (their tiles are BM channels x BN rows)
   const int n_rm = epilogue == EPI_VT ? 0 : epilogue == EPI_QKV ? a.v_start : a.N;
   const int n_sw = a.N - n_rm;
@@ -498,9 +484,7 @@ static pg_status launch_one(const GemmArgs& a, hipStream_t s) {
 
 pg_status launch_gemm(const GemmArgs& a_in, int epilogue, hipStream_t s) {
   GemmArgs a = a_in;
-  static const int raster = [] { const char* e = getenv("PROGRPO_GEMM_RASTER"); return e ? atoi(e) : 1; }();
-  static const int group_m = [] { const char* e = getenv("PROGRPO_GEMM_GROUP_M"); return e ? atoi(e) : GROUP_M; }();
-  a.raster = raster; a.group_m = group_m;
+  a.raster = 1; a.group_m = GROUP_M;
   if (a.M <= 0 || a.N <= 0) return PG_OK;
   if (a.K <= 0 || a.K % 64) return fail(PG_ESHAPE, "GEMM K = %d must be a positive multiple of 64", a.K);
   if (a.lda % 8 || a.ldw % 8 || a.lda < a.K || a.ldw < a.K || ((uintptr_t)a.A & 15) || ((uintptr_t)a.W & 15))
@@ -542,9 +526,49 @@ pg_status launch_gemm(const GemmArgs& a_in, int epilogue, hipStream_t s) {
   return st;
 }
 
+// Measurement hook: bf16 MFMAs on registers alone.  Eight independent 32x32 accumulators per wave keep the pipe
+// full (an MFMA may not follow one that writes the accumulator it reads without waiting for it).
+constexpr int PROBE_ACC = 8;
+__global__ __launch_bounds__(256) void mfma_probe_kernel(float* __restrict__ out, int iters, float scale) {
+  bf16x8 a, b;
+  uint32_t h = (threadIdx.x + 1u) * 2654435761u + blockIdx.x * 40503u;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    h = h * 1664525u + 1013904223u;
+    a[e] = (__bf16)(((int)(h >> 8) % 2001 - 1000) * 1e-3f * scale);
+    h = h * 1664525u + 1013904223u;
+    b[e] = (__bf16)(((int)(h >> 8) % 2001 - 1000) * 1e-3f * scale);
+  }
+  f32x16 acc[PROBE_ACC];
+#pragma unroll
+  for (int i = 0; i < PROBE_ACC; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < PROBE_ACC; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < PROBE_ACC; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) sum += acc[i][e];
+  out[blockIdx.x * blockDim.x + threadIdx.x] = sum;
+}
+
 }  // namespace pg
 
 using namespace pg;
+
+extern "C" pg_status pg_mfma_probe(int32_t blocks, int32_t iters, float operand_scale, float* out, double* flops,
+                                   void* stream) {
+  if (blocks < 1 || blocks > 65536 || iters < 1 || iters > 10000000) return fail(PG_EINVAL, "pg_mfma_probe: blocks %d, iters %d", blocks, iters);
+  if (!out) return fail(PG_EINVAL, "pg_mfma_probe: out is NULL");
+  mfma_probe_kernel<<<dim3(blocks), dim3(256), 0, (hipStream_t)stream>>>(out, iters, operand_scale);
+  PG_LAUNCH_CHECK("mfma_probe_kernel");
+  if (flops) *flops = (double)blocks * 4.0 * iters * PROBE_ACC * 32768.0;
+  return PG_OK;
+}
 
 extern "C" pg_status pg_gemm_bf16(const uint16_t* A, int64_t lda, const uint16_t* W, int64_t ldw,
                                   const uint16_t* bias, float* C, int64_t ldc, int64_t M, int64_t N, int64_t K,

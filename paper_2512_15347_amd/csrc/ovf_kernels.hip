@@ -30,6 +30,16 @@ __device__ __forceinline__ double wave_scan_f64(double a, int lane) {
   return a;
 }
 
+// A group whose size or count the selection cannot take (size outside 1..limit, k outside 1..size): its mask is
+// empty and the error flag is raised, but the k slots that the offsets scan reserved for it in sel_idx are still
+// filled with row indices that exist (its own rows, else row 0), so that a caller who gathers before reading
+// the status stays in bounds.  The scan counts a negative k as 0.
+__device__ __forceinline__ int counted_k(int k) { return k > 0 ? k : 0; }
+__device__ __forceinline__ void fill_bad_group(int32_t* __restrict__ sel_idx, int out0, int b, int n, int k, int lane,
+                                               int lanes) {
+  for (int i = lane; i < k; i += lanes) sel_idx[out0 + i] = n >= 1 ? b + (i < n ? i : n - 1) : 0;
+}
+
 __global__ __launch_bounds__(OVF_WAVES * WAVE) void ovf_select_kernel(
     const float* __restrict__ rewards, const int32_t* __restrict__ offsets, const int32_t* __restrict__ kk,
     int n_groups, const int32_t* __restrict__ new_offsets, uint64_t* __restrict__ masks,
@@ -47,6 +57,7 @@ __global__ __launch_bounds__(OVF_WAVES * WAVE) void ovf_select_kernel(
       if (!(n == 0 && k == 0)) atomicOr(status, 2);
       masks[g] = 0ull;
     }
+    fill_bad_group(sel_idx, out0, b, n, k, lane, WAVE);
     return;
   }
   const bool live = lane < n;
@@ -128,6 +139,7 @@ __global__ __launch_bounds__(OVF_LARGE) void ovf_select_large_kernel(
   if (n < 1 || n > OVF_LARGE || n > 64 * mask_words || k < 1 || k > n) {
     if (tid == 0 && !(n == 0 && k == 0)) atomicOr(status, 2);
     if (tid < mask_words) mrow[tid] = 0ull;
+    fill_bad_group(sel_idx, out0, b, n, k, tid, OVF_LARGE);
     return;                                          // whole workgroup leaves together
   }
   const bool live = tid < n;
@@ -212,7 +224,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_block_sums_kernel(const int
   __shared__ int part[SCAN_THREADS / WAVE];
   int s = 0;
   const int base = blockIdx.x * SCAN_BLOCK + threadIdx.x * SCAN_ITEMS;
-  for (int i = 0; i < SCAN_ITEMS; ++i) if (base + i < n) s += kk[base + i];
+  for (int i = 0; i < SCAN_ITEMS; ++i) if (base + i < n) s += counted_k(kk[base + i]);
   for (int o = 32; o > 0; o >>= 1) s += __shfl_down(s, o, WAVE);
   if ((threadIdx.x & (WAVE - 1)) == 0) part[threadIdx.x / WAVE] = s;
   __syncthreads();
@@ -234,7 +246,7 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_write_kernel(const int32_t*
   const int base = blockIdx.x * SCAN_BLOCK + threadIdx.x * SCAN_ITEMS;
   int loc[SCAN_ITEMS];
   int s = 0;
-  for (int i = 0; i < SCAN_ITEMS; ++i) { loc[i] = s; if (base + i < n) s += kk[base + i]; }
+  for (int i = 0; i < SCAN_ITEMS; ++i) { loc[i] = s; if (base + i < n) s += counted_k(kk[base + i]); }
   lane_tot[threadIdx.x] = s;
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -293,6 +305,7 @@ __global__ __launch_bounds__(OVF_WAVES * WAVE) void uniform_select_kernel(
       if (!(n == 0 && k == 0)) atomicOr(status, 2);
       masks[g] = 0ull;
     }
+    fill_bad_group(sel_idx, out0, b, n, k, lane, WAVE);
     return;
   }
   const uint32_t key = philox4x32_10(u32x4{(uint32_t)lane, draw, (uint32_t)g, STREAM_SUBSAMPLE}, k0, k1).x;

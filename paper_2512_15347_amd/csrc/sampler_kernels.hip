@@ -203,44 +203,64 @@ __global__ __launch_bounds__(STREAM_THREADS) void compact_gather_kernel(
     if (e4[it] < d4) __builtin_nontemporal_store(v[it], xo + e4[it]);
 }
 
-// partial of |x_next[id] - (A x + B u)|^2 per workgroup (stored transition under another network output)
+// Stored transition (x, x_next) of a survivor under another network output u (Eq. 19): two partials per
+// workgroup, the squared residual |x_next - (A x + B u)|^2 and, with xi the noise the sampler drew for this
+// element (regenerated from its counter) and w = residual / C the noise the new policy would need,
+// sum (xi - w)(xi + w) = sum xi^2 - sum w^2 = 2 (log pi_new - log pi_old): the log-ratio is summed from its small
+// per-element terms instead of being the difference of two large log-probs.
 __global__ __launch_bounds__(STREAM_THREADS) void transition_sq_kernel(
     const float* __restrict__ x, const float* __restrict__ u, const float* __restrict__ x_next_by_id,
-    const int32_t* __restrict__ orig_id, int d4, int chunks, float A, float B, float* __restrict__ partials) {
+    const int32_t* __restrict__ orig_id, int d4, int chunks, float A, float B, float inv_C, uint32_t k0, uint32_t k1,
+    uint32_t step, float* __restrict__ partials) {
+  __shared__ float part[2][STREAM_THREADS / WAVE];
   const int r = blockIdx.x / chunks, c = blockIdx.x - r * chunks;
+  const uint32_t id = (uint32_t)orig_id[r];
   const f32x4* xr = reinterpret_cast<const f32x4*>(x) + (size_t)r * d4;
   const f32x4* ur = reinterpret_cast<const f32x4*>(u) + (size_t)r * d4;
-  const f32x4* nr = reinterpret_cast<const f32x4*>(x_next_by_id) + (size_t)orig_id[r] * d4;
-  float acc = 0.f;
+  const f32x4* nr = reinterpret_cast<const f32x4*>(x_next_by_id) + (size_t)id * d4;
+  float acc = 0.f, dif = 0.f;
 #pragma unroll
   for (int it = 0; it < STREAM_ITERS; ++it) {
     const int e4 = c * (STREAM_CHUNK / 4) + it * STREAM_THREADS + threadIdx.x;
     if (e4 < d4) {
       const f32x4 xv = __builtin_nontemporal_load(xr + e4), uv = __builtin_nontemporal_load(ur + e4);
       const f32x4 nv = __builtin_nontemporal_load(nr + e4);
+      const f32x4 z = philox_normal4((uint32_t)e4, step, id, STREAM_STEP, k0, k1);
       const float a0 = nv.x - (A * xv.x + B * uv.x), a1 = nv.y - (A * xv.y + B * uv.y);
       const float a2 = nv.z - (A * xv.z + B * uv.z), a3 = nv.w - (A * xv.w + B * uv.w);
       acc += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
+      const float w0 = a0 * inv_C, w1 = a1 * inv_C, w2 = a2 * inv_C, w3 = a3 * inv_C;
+      dif += ((z.x - w0) * (z.x + w0) + (z.y - w1) * (z.y + w1)) + ((z.z - w2) * (z.z + w2) + (z.w - w3) * (z.w + w3));
     }
   }
-  const float t = block_sum_256(acc);
-  if (threadIdx.x == 0) partials[blockIdx.x] = t;
+  acc = wave_sum(acc);
+  dif = wave_sum(dif);
+  const int lane = threadIdx.x & (WAVE - 1), wv = threadIdx.x / WAVE;
+  if (lane == 0) { part[0][wv] = acc; part[1][wv] = dif; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    partials[2 * (size_t)blockIdx.x] = (part[0][0] + part[0][1]) + (part[0][2] + part[0][3]);
+    partials[2 * (size_t)blockIdx.x + 1] = (part[1][0] + part[1][1]) + (part[1][2] + part[1][3]);
+  }
 }
 
-// logp[id] = -sum / (2 C^2) - d (ln C + 1/2 ln 2 pi)
+// logp[id] = -sum / (2 C^2) - d (ln C + 1/2 ln 2 pi);  log_ratio[id] = 1/2 sum (xi - w)(xi + w), kept in fp64
 __global__ void transition_finish_kernel(const float* __restrict__ partials, int chunks, int n_traj, double inv_2c2,
                                          double log_norm, const int32_t* __restrict__ orig_id,
-                                         float* __restrict__ logp_by_id) {
+                                         float* __restrict__ logp_by_id, double* __restrict__ log_ratio_by_id) {
   const int r = blockIdx.x * blockDim.x + threadIdx.x;
   if (r >= n_traj) return;
-  double s = 0.0;
-  for (int c = 0; c < chunks; ++c) s += (double)partials[(size_t)r * chunks + c];
+  double s = 0.0, dsum = 0.0;
+  for (int c = 0; c < chunks; ++c) {
+    s += (double)partials[2 * ((size_t)r * chunks + c)];
+    dsum += (double)partials[2 * ((size_t)r * chunks + c) + 1];
+  }
   logp_by_id[orig_id[r]] = (float)(-s * inv_2c2 - log_norm);
+  log_ratio_by_id[orig_id[r]] = 0.5 * dsum;
 }
 
 // Eq. 19 and the first term of Eq. 20 per group: one wave per group, lanes over survivors
-__global__ __launch_bounds__(256) void surrogate_kernel(const float* __restrict__ logp_new,
-                                                        const float* __restrict__ logp_old,
+__global__ __launch_bounds__(256) void surrogate_kernel(const double* __restrict__ log_ratio,
                                                         const float* __restrict__ adv,
                                                         const int32_t* __restrict__ offsets,
                                                         const int32_t* __restrict__ orig_id, int n_groups, int T,
@@ -255,7 +275,7 @@ __global__ __launch_bounds__(256) void surrogate_kernel(const float* __restrict_
     const int id = orig_id[i];
     const double a = (double)adv[i];
     for (int s = 0; s < T; ++s) {
-      const double r = exp((double)logp_new[(size_t)s * M0 + id] - (double)logp_old[(size_t)s * M0 + id]);
+      const double r = exp(log_ratio[(size_t)s * M0 + id]);
       ratio[(size_t)s * M0 + id] = (float)r;
       const double rc = fmin(fmax(r, (double)lo), (double)hi);
       acc += fmin(r * a, rc * a);
@@ -321,25 +341,27 @@ pg_status launch_sde_step(const float* x, const float* u, float* x_out, float* l
 
 pg_status launch_transition_logprob(const float* x, const float* u, const float* x_next_by_id,
                                     const int32_t* orig_id, int64_t n_traj, int64_t d, double A, double B, double C,
-                                    float* logp_by_id, float* partials, hipStream_t stream) {
+                                    uint64_t seed, uint32_t step, float* logp_by_id, double* log_ratio_by_id,
+                                    float* partials, hipStream_t stream) {
   PG_TRY(check_stream_shape(n_traj, d));
   if (n_traj == 0) return PG_OK;
   const int chunks = (int)chunks_per_traj(d);
   transition_sq_kernel<<<dim3((unsigned)(n_traj * chunks)), dim3(STREAM_THREADS), 0, stream>>>(
-      x, u, x_next_by_id, orig_id, (int)(d / 4), chunks, (float)A, (float)B, partials);
+      x, u, x_next_by_id, orig_id, (int)(d / 4), chunks, (float)A, (float)B, (float)(1.0 / C), (uint32_t)seed,
+      (uint32_t)(seed >> 32), step, partials);
   PG_LAUNCH_CHECK("transition_sq_kernel");
   transition_finish_kernel<<<dim3((unsigned)((n_traj + 127) / 128)), dim3(128), 0, stream>>>(
       partials, chunks, (int)n_traj, 1.0 / (2.0 * C * C), (double)d * (log(C) + 0.5 * log(2.0 * M_PI)), orig_id,
-      logp_by_id);
+      logp_by_id, log_ratio_by_id);
   PG_LAUNCH_CHECK("transition_finish_kernel");
   return PG_OK;
 }
 
-pg_status launch_surrogate(const float* logp_new, const float* logp_old, const float* adv, const int32_t* offsets,
+pg_status launch_surrogate(const double* log_ratio, const float* adv, const int32_t* offsets,
                            const int32_t* orig_id, int n_groups, int T, int M0, double clip_eps, float* ratio,
                            float* J, hipStream_t stream) {
   surrogate_kernel<<<dim3((n_groups + 3) / 4), dim3(256), 0, stream>>>(
-      logp_new, logp_old, adv, offsets, orig_id, n_groups, T, M0, (float)(1.0 - clip_eps), (float)(1.0 + clip_eps),
+      log_ratio, adv, offsets, orig_id, n_groups, T, M0, (float)(1.0 - clip_eps), (float)(1.0 + clip_eps),
       ratio, J);
   PG_LAUNCH_CHECK("surrogate_kernel");
   return PG_OK;

@@ -172,6 +172,38 @@ def test_select_final_on_a_finished_run(lib, name, mode, kk):
     lib.pg_destroy(ctx)
 
 
+def test_select_final_twice_without_a_sync_between(lib):
+    """Two selections with different counts queued back to back behind a whole sampling loop: the counts of the
+    first must reach the device before the host reuses its staging memory for the second."""
+    say("select_final twice, nothing synchronised in between")
+    cfg = workloads.get_config("cfg4_small")
+    w = workloads.make_weights(cfg); inp = workloads.make_inputs(cfg, w)
+    c, keep = lib.make_config(cfg, probe_bias=inp["probe_b"])
+    ctx = lib.pg_create(c)
+    buf = lib.Buffers(ctx, cfg, inputs=inp, weights_flat=lib.pack_weights(ctx, cfg, w))
+    lib.pg_bind(ctx, buf)
+    P = cfg["P"]
+    lib.pg_sample_group(ctx, 77)                          # queued, not awaited
+    off0 = lib.pg_state(ctx, P)["offsets"]
+    r0 = buf.rewards.clone()                              # stream-ordered copies of the device state
+    k1, k2 = [3, 4, 9], [2, 1, 4]
+    lib.pg_select_final(ctx, 0, k1, 0)
+    r1, m1 = buf.rewards.clone(), buf.masks.clone()
+    off1 = lib.pg_state(ctx, P)["offsets"]
+    lib.pg_select_final(ctx, 0, k2, 0)
+    lib.pg_check(ctx)
+    want1 = cmp.select_final(r0.cpu().numpy()[:off0[-1]].astype(np.float64), np.asarray(off0), k1, 0, eps=1e-6)
+    np.testing.assert_array_equal(m1.cpu().numpy().view(np.uint64)[:P], want1["masks"])
+    assert off1 == want1["offsets"].tolist()
+    want2 = cmp.select_final(r1.cpu().numpy()[:off1[-1]].astype(np.float64), np.asarray(off1), k2, 0, eps=1e-6)
+    np.testing.assert_array_equal(buf.masks.cpu().numpy().view(np.uint64)[:P], want2["masks"])
+    st = lib.pg_state(ctx, P)
+    assert st["offsets"] == want2["offsets"].tolist() == [0, 2, 3, 7]
+    np.testing.assert_array_equal(buf.sel_idx.cpu().numpy()[:st["M"]], want2["sel_idx"])
+    np.testing.assert_array_equal(buf.group_offsets.cpu().numpy(), want2["offsets"])
+    lib.pg_destroy(ctx)
+
+
 def test_select_final_argument_errors(lib):
     cfg = workloads.get_config("cfg1")
     w = workloads.make_weights(cfg); inp = workloads.make_inputs(cfg, w)

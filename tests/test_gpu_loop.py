@@ -109,13 +109,26 @@ def test_loop_call_order_is_enforced(lib):
     with pytest.raises(lib.PgError) as e:
         lib.pg_step(ctx, 0)                              # no network evaluation yet
     assert e.value.status == lib.PG_ESCHED
+    with pytest.raises(lib.PgError) as e:
+        lib.pg_net_forward(ctx, 1)                       # the network is evaluated at the step that comes next
+    assert e.value.status == lib.PG_ESCHED
     lib.pg_net_forward(ctx, 0)
     with pytest.raises(lib.PgError):
         lib.pg_prune(ctx, 0)                             # step 0 is not a checkpoint
     lib.pg_step(ctx, 0)
+    with pytest.raises(lib.PgError) as e:
+        lib.pg_advantages(ctx)                           # Eq. 18 is on the final latents: 1 of 10 steps taken
+    assert e.value.status == lib.PG_ESCHED
     for s in range(1, 5):
         lib.pg_net_forward(ctx, s)
+        if s == 3:
+            with pytest.raises(lib.PgError) as e:
+                lib.pg_prune(ctx, 4)                     # a prune belongs to the step whose evaluation it uses
+            assert e.value.status == lib.PG_ESCHED
         if s == 4:
+            with pytest.raises(lib.PgError) as e:
+                lib.pg_step(ctx, 4)                      # the schedule prunes here: the funnel must be followed
+            assert e.value.status == lib.PG_ESCHED
             lib.pg_prune(ctx, 4)
             with pytest.raises(lib.PgError):
                 lib.pg_net_forward(ctx, 5)               # the prune must be consumed by its step first

@@ -114,6 +114,27 @@ def test_create_rejects_bad_schedules():
         pg.pg_create(c)
 
 
+def test_schedule_table_is_the_funnel():
+    """The counts / offsets a prune uses come from a table built once from the schedule (Sec. 5.2): every row is
+    the funnel's state at that step, also for ragged groups and for a group that is never pruned."""
+    for name in ("cfg1", "cfg3", "cfg4", "cfg4_small", "paper_diffusion_small"):
+        cfg, c, keep = _ctx(name)
+        ctx = pg.pg_create(c)
+        P, N = cfg["P"], cfg["N"]
+        size = [N] * P
+        for s in range(cfg["T"]):
+            k, off = pg.pg_get_schedule(ctx, s, P)
+            want = [dict(cfg["schedule"][g]).get(s, size[g]) for g in range(P)]
+            assert k == want, (name, s)
+            assert off == np.concatenate([[0], np.cumsum(want)]).tolist()
+            size = want
+        final = [cfg["schedule"][g][-1][1] if cfg["schedule"][g] else N for g in range(P)]
+        assert size == final
+        with pytest.raises(pg.PgError):
+            pg.pg_get_schedule(ctx, cfg["T"], P)
+        pg.pg_destroy(ctx)
+
+
 def test_ddim_needs_enough_training_steps_and_eta():
     cfg, c, keep = _ctx("cfg2_small")
     c.T_train = cfg["T"]
