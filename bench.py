@@ -52,7 +52,9 @@ def cpu_baseline(cfg, w, inp, seed, budget_traj):
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     return dict(value=n / dt, unit="trajectory-steps/s", cores=int(threads), kind="oracle",
                 sample=f"{n} trajectories of group 0, one full step (network + preview/OVF + update/log-prob) in {dt:.1f} s",
-                s_per_group=workloads_evals(cfg) / (n / dt) / cfg["P"])
+                s_per_group_extrapolated=workloads_evals(cfg) / (n / dt) / cfg["P"],
+                note="s_per_group_extrapolated = this sample's rate applied to all trajectory-steps of a group-batch; "
+                     "the oracle did not run a whole group")
 
 
 def stream_kernels_at_stress_shape(pg, torch, n=1024, d=16 * 128 * 128, reps=10):
@@ -210,12 +212,62 @@ def policy_ratio_pass(pg, torch, cfg, w, inp, seed):
     return out
 
 
+def mfma_register_loop(pg, torch, reps=3):
+    """A loop of bf16 MFMAs on registers alone (no LDS, no memory): what the matrix pipes of this part sustain with
+    all-zero and with random operands.  The published peak assumes the nominal clock; under a dense MFMA load the
+    part runs below it, the more so the more operand bits toggle."""
+    out = torch.zeros(512 * 256, device="cuda:0")
+    res = {}
+    for name, scale in (("zeros", 0.0), ("random", 1.0)):
+        best = 0.0
+        for _ in range(reps):
+            pg.pg_mfma_probe(512, 2000, scale, out)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flops = pg.pg_mfma_probe(512, 20000, scale, out)
+            e1.record()
+            torch.cuda.synchronize()
+            best = max(best, flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        res[name + "_tflops"] = round(best, 1)
+    return res
+
+
+def gemm_alone(pg, torch, M=8192, N=8192, K=8192, reps=20, blocks=3):
+    """The GEMM entry point alone on one large shape with all-zero, small-integer and N(0, 1) operands."""
+    res = {}
+    for kind in ("random", "ints", "zeros"):
+        if kind == "random":
+            A = torch.randn(M, K, device="cuda"); W = torch.randn(N, K, device="cuda") * 0.02
+        elif kind == "ints":
+            A = torch.randint(-2, 3, (M, K), device="cuda").float(); W = torch.randint(-2, 3, (N, K), device="cuda").float()
+        else:
+            A = torch.zeros(M, K, device="cuda"); W = torch.zeros(N, K, device="cuda")
+        A = A.to(torch.bfloat16).view(torch.int16); W = W.to(torch.bfloat16).view(torch.int16)
+        Cm = torch.empty(M, N, device="cuda")
+        for _ in range(3):
+            pg.pg_gemm_bf16(A, K, W, K, None, Cm, N, M, N, K)
+        torch.cuda.synchronize()
+        runs = []
+        for _ in range(blocks):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                pg.pg_gemm_bf16(A, K, W, K, None, Cm, N, M, N, K)
+            e1.record()
+            torch.cuda.synchronize()
+            runs.append(round(2.0 * M * N * K / (e0.elapsed_time(e1) / reps) / 1e9, 1))
+        res[kind + "_tflops"] = runs
+        del A, W, Cm
+    return res
+
+
 def recorded_gemm_traffic(workload):
     """HBM bytes per GEMM launch from the committed counter summary, or None when there is none for this
     workload or the kernel source has changed since the counters were taken."""
     import hashlib
     import re
-    path = os.path.join(ROOT, "profiles", f"gemm_kernel_{workload}_hbm_traffic.txt")
+    path = os.path.join(ROOT, "profiles", f"gemm_kernel_{workload}_loop_hbm_traffic.txt")
     if not os.path.exists(path):
         return None
     text = open(path).read()
@@ -239,7 +291,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg2", choices=sorted(DESCRIPTIONS))
+    ap.add_argument("--workload", default="cfg4", choices=sorted(DESCRIPTIONS),
+                    help="cfg4 (the largest configuration, 8 prompts x 48 trajectories on the 1536-wide network) is the headline")
+    ap.add_argument("--bracket-batches", type=int, default=3,
+                    help="group-batches of the second pass in which every heavy launch is bracketed by events")
+    ap.add_argument("--gemm-alone", action="store_true", help="also time the GEMM entry point alone at 8192^3 with zero / integer / normal operands")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-arms", action="store_true", help="skip the comparison arms (full group, uniform subset, static OVF)")
     ap.add_argument("--cpu-sample", type=int, default=0, help="trajectories in the oracle sample (0 = auto)")
@@ -282,10 +338,11 @@ def main():
 
     # the same K group-batches once more with every heavy launch bracketed by HIP events on its stream
     # (the brackets cost about a tenth of the loop's wall time, so they stay out of `value`)
+    n_br = max(1, min(args.steps, args.bracket_batches))
     pg.pg_profile_begin(1 << 18)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    for i in range(args.steps):
+    for i in range(n_br):
         pg.pg_sample_group(ctx, seed + 100 + i)
     torch.cuda.synchronize()
     dt_prof = time.perf_counter() - t1
@@ -301,7 +358,12 @@ def main():
                     peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
                     traffic=recorded_gemm_traffic(args.workload),
                     launches=g["launches"], avg_launch_us=round(1e3 * g["ms"] / max(g["launches"], 1), 2),
-                    share_of_step_time=round(g["ms"] * 1e-3 / dt_prof, 4), bracketed_pass_ms_per_step=round(1e3 * dt_prof / args.steps, 3))
+                    share_of_step_time=round(g["ms"] * 1e-3 / dt_prof, 4), bracketed_batches=n_br,
+                    bracketed_pass_ms_per_step=round(1e3 * dt_prof / n_br, 3))
+    # the same figure against what a loop of MFMAs alone sustains on this part with random operands
+    reg = mfma_register_loop(pg, torch)
+    roofline["mfma_register_loop"] = reg
+    roofline["frac_of_register_loop_random"] = round(gemm_tflops / reg["random_tflops"], 4) if reg["random_tflops"] > 0 else None
     others = dict(
         attention=dict(tflops=round(a["work"] / (a["ms"] * 1e-3) / 1e12, 2) if a["ms"] > 0 else None,
                        share_of_step_time=round(a["ms"] * 1e-3 / dt_prof, 4), launches=a["launches"]),
@@ -324,6 +386,8 @@ def main():
     if not args.no_arms:
         out["comparison_arms"] = comparison_arms(pg, torch, workloads, cfg, w, inp, seed, ctx, buf)
         out["policy_ratio"] = policy_ratio_pass(pg, torch, cfg, w, inp, seed)
+    if args.gemm_alone:
+        out["gemm_alone_8192"] = gemm_alone(pg, torch)
     if not args.no_cpu_baseline:
         budget = args.cpu_sample or {"cfg1": 8, "cfg2": 8}.get(args.workload, 1)
         out["cpu_baseline"] = cpu_baseline(cfg, w, inp, seed, budget)
