@@ -210,7 +210,7 @@ __global__ __launch_bounds__(STREAM_THREADS) void compact_gather_kernel(
 // per-element terms instead of being the difference of two large log-probs.
 __global__ __launch_bounds__(STREAM_THREADS) void transition_sq_kernel(
     const float* __restrict__ x, const float* __restrict__ u, const float* __restrict__ x_next_by_id,
-    const int32_t* __restrict__ orig_id, int d4, int chunks, float A, float B, float inv_C, uint32_t k0, uint32_t k1,
+    const int32_t* __restrict__ orig_id, int d4, int chunks, float A, float B, float C, uint32_t k0, uint32_t k1,
     uint32_t step, float* __restrict__ partials) {
   __shared__ float part[2][STREAM_THREADS / WAVE];
   const int r = blockIdx.x / chunks, c = blockIdx.x - r * chunks;
@@ -229,7 +229,9 @@ __global__ __launch_bounds__(STREAM_THREADS) void transition_sq_kernel(
       const float a0 = nv.x - (A * xv.x + B * uv.x), a1 = nv.y - (A * xv.y + B * uv.y);
       const float a2 = nv.z - (A * xv.z + B * uv.z), a3 = nv.w - (A * xv.w + B * uv.w);
       acc += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
-      const float w0 = a0 * inv_C, w1 = a1 * inv_C, w2 = a2 * inv_C, w3 = a3 * inv_C;
+      // divided by the very fp32 scale the sampler multiplied its noise with: a rounded reciprocal would bias every
+      // term the same way, and the bias would add up over the d elements
+      const float w0 = a0 / C, w1 = a1 / C, w2 = a2 / C, w3 = a3 / C;
       dif += ((z.x - w0) * (z.x + w0) + (z.y - w1) * (z.y + w1)) + ((z.z - w2) * (z.z + w2) + (z.w - w3) * (z.w + w3));
     }
   }
@@ -347,7 +349,7 @@ pg_status launch_transition_logprob(const float* x, const float* u, const float*
   if (n_traj == 0) return PG_OK;
   const int chunks = (int)chunks_per_traj(d);
   transition_sq_kernel<<<dim3((unsigned)(n_traj * chunks)), dim3(STREAM_THREADS), 0, stream>>>(
-      x, u, x_next_by_id, orig_id, (int)(d / 4), chunks, (float)A, (float)B, (float)(1.0 / C), (uint32_t)seed,
+      x, u, x_next_by_id, orig_id, (int)(d / 4), chunks, (float)A, (float)B, (float)C, (uint32_t)seed,
       (uint32_t)(seed >> 32), step, partials);
   PG_LAUNCH_CHECK("transition_sq_kernel");
   transition_finish_kernel<<<dim3((unsigned)((n_traj + 127) / 128)), dim3(128), 0, stream>>>(
