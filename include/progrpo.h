@@ -263,6 +263,19 @@ pg_status pg_ovf_select(const float *rewards, const int32_t *group_offsets, cons
                         int32_t n_groups, uint64_t *masks, int32_t *sel_idx, int32_t *new_offsets,
                         int32_t *status, int32_t *scratch, void *stream);
 
+/* pg_ovf_select for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): same arguments less `scratch`, same results.  The block sums of the
+ * offsets scan live in a device array inside the library (PG_OVF_NOALLOC_MAX_GROUPS / 2048 + 1 words, 8 KiB, one
+ * copy per GPU for the life of the process), so at most PG_OVF_NOALLOC_MAX_GROUPS groups per call: more is
+ * rejected with PG_ESHAPE before anything is launched.  The call allocates and frees nothing.  It runs on the
+ * CURRENT device, which must be the stream's (else PG_EINVAL); the first call on a device looks the array's
+ * address up (not under stream capture).  Every call on a GPU uses that GPU's one array: calls that overlap in
+ * time on one GPU (different streams or threads) race; calls on one stream are ordered and safe. */
+#define PG_OVF_NOALLOC_MAX_GROUPS 4194304
+pg_status pg_ovf_select_noalloc(const float *rewards, const int32_t *group_offsets, const int32_t *k,
+                                int32_t n_groups, uint64_t *masks, int32_t *sel_idx, int32_t *new_offsets,
+                                int32_t *status, void *stream);
+
 /* pg_ovf_select for groups of up to 1024 members (a generalisation: the paper's groups have at
  * most 64).  masks: [n_groups, mask_words] uint64, bit i of word w = slot 64 w + i, groups must
  * fit (size <= 64 * mask_words, 1 <= mask_words <= 16).  Same evaluation order, with the prefix

@@ -92,6 +92,7 @@ _SIGNATURES = {
     "pg_preview_reward": (_i32, [_vp, _vp, _vp, _vp, _i64, _i64, _f64, _f64, _f64, _vp, _vp]),
     "pg_ovf_scratch_ints": (_i64, [_i64]),
     "pg_ovf_select": (_i32, [_vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "pg_ovf_select_noalloc": (_i32, [_vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
     "pg_ovf_select_large": (_i32, [_vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "pg_uniform_select": (_i32, [_vp, _vp, _i32, _u64, _u32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "pg_group_stats": (_i32, [_vp, _vp, _i32, _f64, _vp, _vp, _vp]),
@@ -378,6 +379,14 @@ def pg_ovf_scratch_ints(n_groups):
 def pg_ovf_select(rewards, group_offsets, k, n_groups, masks, sel_idx, new_offsets, status, scratch, stream=None):
     _check(_lib.pg_ovf_select(_ptr(rewards), _ptr(group_offsets), _ptr(k), n_groups, _ptr(masks), _ptr(sel_idx),
                               _ptr(new_offsets), _ptr(status), _ptr(scratch), _stream(stream)))
+
+
+PG_OVF_NOALLOC_MAX_GROUPS = 4194304
+
+
+def pg_ovf_select_noalloc(rewards, group_offsets, k, n_groups, masks, sel_idx, new_offsets, status, stream=None):
+    _check(_lib.pg_ovf_select_noalloc(_ptr(rewards), _ptr(group_offsets), _ptr(k), n_groups, _ptr(masks), _ptr(sel_idx),
+                                      _ptr(new_offsets), _ptr(status), _stream(stream)))
 
 
 def pg_ovf_select_large(rewards, group_offsets, k, n_groups, mask_words, masks, sel_idx, new_offsets, status, scratch,

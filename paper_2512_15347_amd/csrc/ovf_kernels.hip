@@ -6,6 +6,7 @@
 // six-step shuffle-up scan, k+1 candidate scores in lanes 0..k, a butterfly arg-max, and a ballot
 // for the survivor mask.  Why k+1 candidates are enough: with the other members fixed the variance
 // is a convex quadratic in one member's value, so some optimum is "j lowest and k-j highest".
+#include <mutex>
 #include "common.hpp"
 #include "philox.hpp"
 
@@ -469,6 +470,55 @@ extern "C" pg_status pg_ovf_select(const float* rewards, const int32_t* group_of
     return fail(PG_EINVAL, "pg_ovf_select: null pointer");
   hipStream_t s = (hipStream_t)stream;
   PG_TRY(scan_k(k, n_groups, scratch, new_offsets, s));
+  return launch_ovf(rewards, group_offsets, k, n_groups, new_offsets, masks, sel_idx, status, s);
+}
+
+// ---- the same selection for callers that cannot allocate: the scan's block sums live in a file-scope device
+// array (one copy per GPU, held until the process ends) instead of a buffer the caller brings ----
+constexpr int NOALLOC_SCRATCH_INTS = PG_OVF_NOALLOC_MAX_GROUPS / SCAN_BLOCK + 1;
+static __device__ __align__(256) int32_t g_ovf_scratch[NOALLOC_SCRATCH_INTS];
+
+// On the host the array's name stands for the symbol, not for device memory: its address on a GPU is looked up
+// once per device (with that device current) and kept.
+constexpr int MAX_DEVICES = 64;
+static int32_t* g_ovf_scratch_ptr[MAX_DEVICES] = {};
+static std::mutex g_ovf_scratch_mu;
+
+static pg_status ovf_scratch_on_current_device(hipStream_t s, int32_t** out) {
+  int dev = -1;
+  PG_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return fail(PG_EHIP, "pg_ovf_select_noalloc: device index %d", dev);
+  if (s) {
+    int sdev = -1;
+    PG_HIP(hipStreamGetDevice(s, &sdev));
+    if (sdev != dev)
+      return fail(PG_EINVAL, "pg_ovf_select_noalloc: the stream belongs to device %d, the current device is %d", sdev, dev);
+  }
+  std::lock_guard<std::mutex> lock(g_ovf_scratch_mu);
+  if (!g_ovf_scratch_ptr[dev]) {
+    void* p = nullptr;
+    PG_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(g_ovf_scratch)));
+    if (!p) return fail(PG_EHIP, "pg_ovf_select_noalloc: the scratch symbol has no address on device %d", dev);
+    g_ovf_scratch_ptr[dev] = static_cast<int32_t*>(p);
+  }
+  *out = g_ovf_scratch_ptr[dev];
+  return PG_OK;
+}
+
+extern "C" pg_status pg_ovf_select_noalloc(const float* rewards, const int32_t* group_offsets, const int32_t* k,
+                                           int32_t n_groups, uint64_t* masks, int32_t* sel_idx,
+                                           int32_t* new_offsets, int32_t* status, void* stream) {
+  if (n_groups < 0) return fail(PG_EINVAL, "pg_ovf_select_noalloc: n_groups = %d", n_groups);
+  if (n_groups > PG_OVF_NOALLOC_MAX_GROUPS)
+    return fail(PG_ESHAPE, "pg_ovf_select_noalloc: %d groups exceed the built-in scratch (at most %d); use pg_ovf_select",
+                n_groups, PG_OVF_NOALLOC_MAX_GROUPS);
+  if (n_groups == 0) return PG_OK;
+  if (!rewards || !group_offsets || !k || !masks || !sel_idx || !new_offsets || !status)
+    return fail(PG_EINVAL, "pg_ovf_select_noalloc: null pointer");
+  hipStream_t s = (hipStream_t)stream;
+  int32_t* sums = nullptr;
+  PG_TRY(ovf_scratch_on_current_device(s, &sums));
+  PG_TRY(scan_k(k, n_groups, sums, new_offsets, s));          // every word it reads back it has written in this call
   return launch_ovf(rewards, group_offsets, k, n_groups, new_offsets, masks, sel_idx, status, s);
 }
 

@@ -184,6 +184,9 @@ def test_context_free_argument_checks_need_no_gpu():
                                        None, None) == pg.PG_EINVAL          # null pointers
     assert pg._lib.pg_ovf_select(None, None, None, -1, None, None, None, None, None, None) == pg.PG_EINVAL
     assert pg._lib.pg_ovf_select(None, None, None, 0, None, None, None, None, None, None) == pg.PG_OK
+    assert pg._lib.pg_ovf_select_noalloc(None, None, None, pg.PG_OVF_NOALLOC_MAX_GROUPS + 1, None, None, None, None,
+                                         None) == pg.PG_ESHAPE              # beyond the built-in scratch
+    assert "at most" in pg.pg_last_error()
     assert pg._lib.pg_compact_gather(None, None, None, 0, 16, None) == pg.PG_OK      # empty input
     assert pg._lib.pg_group_advantages(None, None, 3, -1.0, None, None) == pg.PG_EINVAL
     assert pg.pg_step_scratch_floats(1024, 262144) == 1024 * 64
