@@ -17,6 +17,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+PEAK_VALU_LANE_OPS = 256 * 64 * 2.4e9       # vector-ALU issue roofline: 256 compute units x 64 lanes x 2.4 GHz
+# Vector-ALU instructions per latent element of the two kernels that the Philox / Box-Muller arithmetic bounds, as
+# the SQ_INSTS_VALU counter reads them (profiles/attention_and_streaming_kernels_issue_counters.txt)
+VALU_OPS_PER_ELEMENT = {"init_latents": 20.81, "sde_step_bf16": 33.94}
 
 DESCRIPTIONS = {
     "cfg1": "tiny flow group 8->4, DiT 64 tok x 128 x 2 blocks",
@@ -95,6 +99,11 @@ def stream_kernels_at_stress_shape(pg, torch, n=1024, d=16 * 128 * 128, reps=10)
     res["sde_step_logprob_bf16_storage_1024x16x128x128"] = timed(
         lambda: pg.pg_sde_step_logprob_bf16(xb, ub, xob, None, None, None, None, ids, n, d, 0.93, -0.1, 0.38, 7, 3, part), 6.0 * n * d)
     res["init_latents_1024x16x128x128"] = timed(lambda: pg.pg_init_latents(xo, ids, 7), 4.0 * n * d)
+    # these two issue vector-ALU instructions in (nearly) every cycle: their roofline is the ALU's, not the memory's
+    for key, name in (("init_latents_1024x16x128x128", "init_latents"), ("sde_step_logprob_bf16_storage_1024x16x128x128", "sde_step_bf16")):
+        ops = VALU_OPS_PER_ELEMENT[name]
+        res[key].update(bound="alu", valu_ops_per_element=ops,
+                        alu_frac=round(ops * n * d / (res[key]["us"] * 1e-6) / PEAK_VALU_LANE_OPS, 4))
     # the plain copy above is the practical ceiling for a kernel that reads and writes in equal parts
     res["sde_step_vs_copy_ceiling"] = round(res["sde_step_logprob_1024x16x128x128"]["gbs"] / res["compact_gather_1024_to_512"]["gbs"], 3)
     return res
@@ -212,6 +221,78 @@ def policy_ratio_pass(pg, torch, cfg, w, inp, seed):
     return out
 
 
+class PowerMeter:
+    """Socket power from the driver's hwmon file (microwatts), polled from a host thread at about 50 Hz while a
+    phase runs.  The part has a package power limit (hwmon power1_cap); a dense MFMA load on random operands runs
+    into it, and then throughput is set by energy per flop, not by cycles."""
+
+    def __init__(self):
+        import glob
+        files = glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input")
+        self.path = files[0] if files else None
+        caps = glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_cap")
+        self.cap_w = None
+        if caps:
+            try:
+                self.cap_w = int(open(caps[0]).read()) / 1e6
+            except (OSError, ValueError):
+                pass
+        self.samples = []
+        self._stop = False
+        self._thread = None
+
+    def _poll(self):
+        while not self._stop:
+            try:
+                self.samples.append((time.perf_counter(), int(open(self.path).read()) / 1e6))
+            except (OSError, ValueError):
+                pass
+            time.sleep(0.02)
+
+    def start(self):
+        if self.path is None:
+            return
+        import threading
+        self._stop = False
+        self._thread = threading.Thread(target=self._poll, daemon=True)
+        self._thread.start()
+
+    def stop(self):
+        if self._thread is not None:
+            self._stop = True
+            self._thread.join()
+            self._thread = None
+
+    def window(self, t0, t1):
+        """Mean and maximum power between two perf_counter readings (the first fifth of the window is left out:
+        the power controller takes that long to settle), or None without telemetry."""
+        w = [p for (t, p) in self.samples if t0 + 0.2 * (t1 - t0) <= t <= t1]
+        if not w:
+            return None
+        return dict(mean_w=round(sum(w) / len(w), 1), max_w=round(max(w), 1), samples=len(w))
+
+
+def sustained(pg, torch, meter, fn, flops_per_call, seconds=2.0):
+    """fn() queued back to back for about `seconds`: TFLOP/s and the socket power meanwhile."""
+    for _ in range(3):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    n = 0
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(10):
+            fn()
+        n += 10
+        torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    out = dict(tflops=round(flops_per_call * n / (t1 - t0) / 1e12, 1))
+    pw = meter.window(t0, t1)
+    if pw:
+        out.update(power_mean_w=pw["mean_w"], power_max_w=pw["max_w"])
+    time.sleep(0.5)
+    return out
+
+
 def mfma_register_loop(pg, torch, reps=3):
     """A loop of bf16 MFMAs on registers alone (no LDS, no memory): what the matrix pipes of this part sustain with
     all-zero and with random operands.  The published peak assumes the nominal clock; under a dense MFMA load the
@@ -233,32 +314,32 @@ def mfma_register_loop(pg, torch, reps=3):
     return res
 
 
-def gemm_alone(pg, torch, M=8192, N=8192, K=8192, reps=20, blocks=3):
-    """The GEMM entry point alone on one large shape with all-zero, small-integer and N(0, 1) operands."""
+def power_legs(pg, torch, meter, shapes):
+    """Sustained (about 2 s each) runs with the socket power beside them: the register-only MFMA loop with zero and
+    with random operands, and the GEMM entry point alone with zero / small-integer / N(0, 1) operands."""
     res = {}
-    for kind in ("random", "ints", "zeros"):
-        if kind == "random":
-            A = torch.randn(M, K, device="cuda"); W = torch.randn(N, K, device="cuda") * 0.02
-        elif kind == "ints":
-            A = torch.randint(-2, 3, (M, K), device="cuda").float(); W = torch.randint(-2, 3, (N, K), device="cuda").float()
-        else:
-            A = torch.zeros(M, K, device="cuda"); W = torch.zeros(N, K, device="cuda")
-        A = A.to(torch.bfloat16).view(torch.int16); W = W.to(torch.bfloat16).view(torch.int16)
-        Cm = torch.empty(M, N, device="cuda")
-        for _ in range(3):
-            pg.pg_gemm_bf16(A, K, W, K, None, Cm, N, M, N, K)
-        torch.cuda.synchronize()
-        runs = []
-        for _ in range(blocks):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(reps):
-                pg.pg_gemm_bf16(A, K, W, K, None, Cm, N, M, N, K)
-            e1.record()
-            torch.cuda.synchronize()
-            runs.append(round(2.0 * M * N * K / (e0.elapsed_time(e1) / reps) / 1e9, 1))
-        res[kind + "_tflops"] = runs
-        del A, W, Cm
+    out = torch.zeros(512 * 256, device="cuda:0")
+    fl = 512 * 4.0 * 20000 * 8 * 32768.0
+    res["mfma_register_loop_zeros"] = sustained(pg, torch, meter, lambda: pg.pg_mfma_probe(512, 20000, 0.0, out), fl)
+    res["mfma_register_loop_random"] = sustained(pg, torch, meter, lambda: pg.pg_mfma_probe(512, 20000, 1.0, out), fl)
+    for (M, N, K) in shapes:
+        kinds = ("random", "ints", "zeros") if (M, N, K) == shapes[0] else ("random",)
+        for kind in kinds:
+            if kind == "random":
+                A = torch.randn(M, K, device="cuda"); W = torch.randn(N, K, device="cuda") * 0.02
+            elif kind == "ints":
+                A = torch.randint(-2, 3, (M, K), device="cuda").float(); W = torch.randint(-2, 3, (N, K), device="cuda").float()
+            else:
+                A = torch.zeros(M, K, device="cuda"); W = torch.zeros(N, K, device="cuda")
+            A = A.to(torch.bfloat16).view(torch.int16); W = W.to(torch.bfloat16).view(torch.int16)
+            Cm = torch.empty(M, N, device="cuda")
+            res[f"gemm_{M}x{N}x{K}_{kind}"] = sustained(
+                pg, torch, meter, lambda: pg.pg_gemm_bf16(A, K, W, K, None, Cm, N, M, N, K), 2.0 * M * N * K)
+            del A, W, Cm
+    x = torch.randn(1024, 1 << 18, device="cuda"); y = torch.empty_like(x)
+    src = torch.arange(0, 1024, dtype=torch.int32, device="cuda")
+    res["copy_2GiB_of_traffic"] = sustained(pg, torch, meter, lambda: pg.pg_compact_gather(x, y, src, 1024, 1 << 18), 0.0)
+    res["copy_2GiB_of_traffic"].pop("tflops")
     return res
 
 
@@ -295,7 +376,9 @@ def main():
                     help="cfg4 (the largest configuration, 8 prompts x 48 trajectories on the 1536-wide network) is the headline")
     ap.add_argument("--bracket-batches", type=int, default=3,
                     help="group-batches of the second pass in which every heavy launch is bracketed by events")
-    ap.add_argument("--gemm-alone", action="store_true", help="also time the GEMM entry point alone at 8192^3 with zero / integer / normal operands")
+    ap.add_argument("--power-legs", action="store_true",
+                    help="also run, for about 2 s each with the socket power beside them, the register-only MFMA loop and the "
+                         "GEMM entry point alone (8192^3 with zero / integer / normal operands, two shapes of the 1536-wide network)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-arms", action="store_true", help="skip the comparison arms (full group, uniform subset, static OVF)")
     ap.add_argument("--cpu-sample", type=int, default=0, help="trajectories in the oracle sample (0 = auto)")
@@ -326,12 +409,16 @@ def main():
     torch.cuda.synchronize()
 
     # timed region: K whole group-batches, nothing but the library's own launches on the stream
+    # (a host thread reads the socket power from sysfs meanwhile; it touches neither the GPU nor the stream)
+    meter = PowerMeter()
+    meter.start()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         pg.pg_sample_group(ctx, seed + 100 + i)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    power = meter.window(t0, t0 + dt)
     pg.pg_check(ctx)
     st = pg.pg_state(ctx, cfg["P"])
     assert st["evals"] == evals, (st, evals)
@@ -386,8 +473,12 @@ def main():
     if not args.no_arms:
         out["comparison_arms"] = comparison_arms(pg, torch, workloads, cfg, w, inp, seed, ctx, buf)
         out["policy_ratio"] = policy_ratio_pass(pg, torch, cfg, w, inp, seed)
-    if args.gemm_alone:
-        out["gemm_alone_8192"] = gemm_alone(pg, torch)
+    if power:
+        out["power"] = dict(socket_cap_w=meter.cap_w, timed_region_mean_w=power["mean_w"], timed_region_max_w=power["max_w"],
+                            source="hwmon power1_input polled at 50 Hz by a host thread")
+    if args.power_legs:
+        out["power_legs"] = power_legs(pg, torch, meter, [(8192, 8192, 8192), (56544, 4608, 1536), (56544, 1536, 6144)])
+    meter.stop()
     if not args.no_cpu_baseline:
         budget = args.cpu_sample or {"cfg1": 8, "cfg2": 8}.get(args.workload, 1)
         out["cpu_baseline"] = cpu_baseline(cfg, w, inp, seed, budget)
