@@ -383,10 +383,9 @@ extern "C" pg_status pg_bind(pg_ctx* c, const pg_buffers* b) {
       ((uintptr_t)b->u & 15) || ((uintptr_t)b->probe_w & 15) || ((uintptr_t)b->weights & 15) ||
       ((uintptr_t)b->ctx & 15))
     return fail(PG_ESHAPE, "pg_bind: buffers must be 16-byte aligned (workspace 256)");
-  if (!c->staging) {
+  if (!c->staging)
     PG_HIP(hipHostMalloc((void**)&c->staging, (size_t)(2 * c->cfg.P + 1) * sizeof(int32_t), hipHostMallocDefault));
-    PG_HIP(hipEventCreateWithFlags(&c->staging_read, hipEventDisableTiming));
-  }
+  if (!c->staging_read) PG_HIP(hipEventCreateWithFlags(&c->staging_read, hipEventDisableTiming));
   c->buf = *b;
   // the schedule's counts and offsets live in the workspace from here on (synchronous copies: pg_bind is set-up)
   {
