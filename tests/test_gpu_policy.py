@@ -84,7 +84,8 @@ def test_trajectory_record_and_policy_ratio(lib, name):
     lp = logp_new.cpu().numpy().astype(np.float64)
     np.testing.assert_allclose(lp[:, ids], want["logp_new"][:, ids], rtol=1e-3)
     r = ratio.cpu().numpy().astype(np.float64)
-    log_r = np.log(r[:, ids])
+    with np.errstate(divide="ignore"):                     # the last diffusion step's ratio underflows to 0; it is not compared
+        log_r = np.log(r[:, ids])
     log_w = np.log(want["ratio"][:, ids])
     assert np.max(np.abs(log_w[good])) > 1e-2                # the update is visible
     for s_ in good:
