@@ -33,6 +33,11 @@ DESCRIPTIONS = {
 }
 
 
+def progress(msg):
+    """Stage marker on stderr (stdout carries the one JSON line): a long run must show that it is alive."""
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
 def cpu_baseline(cfg, w, inp, seed, budget_traj):
     """The oracle, as it stands, on a bounded sample: `budget_traj` trajectories of the first group for
     one whole step (network evaluation, preview + proxy reward, OVF over the sample, update + log-prob)."""
@@ -387,6 +392,7 @@ def main():
         sys.exit("this library runs on ONE GPU: the path has no inter-GPU part (groups are independent and would "
                  "shard by prompt); run with --gpus 1")
 
+    progress("importing torch and loading the library")
     import numpy as np
     import torch
     from paper_2512_15347_amd.build import ensure_built
@@ -395,17 +401,20 @@ def main():
 
     cfg = workloads.get_config(args.workload)
     seed = workloads.MASTER_SEED
+    progress(f"workload {args.workload}: drawing the synthetic network weights and inputs")
     w = workloads.make_weights(cfg)
     inp = workloads.make_inputs(cfg, w)
     c, keep = pg.make_config(cfg, probe_bias=inp["probe_b"])
     ctx = pg.pg_create(c)
+    progress(f"packing {pg.pg_weights_numel(ctx) / 1e6:.0f} M weights, workspace {pg.pg_workspace_bytes(ctx) / 2**30:.2f} GiB")
     buf = pg.Buffers(ctx, cfg, inputs=inp, weights_flat=pg.pack_weights(ctx, cfg, w))
     pg.pg_bind(ctx, buf)
     evals = workloads.network_evals(cfg)
 
     for i in range(args.warmup):
         pg.pg_sample_group(ctx, seed + i)
-    pg.pg_check(ctx)
+        pg.pg_check(ctx)
+        progress(f"warm-up group-batch {i + 1} of {args.warmup} done")
     torch.cuda.synchronize()
 
     # timed region: K whole group-batches, nothing but the library's own launches on the stream
@@ -413,9 +422,14 @@ def main():
     meter = PowerMeter()
     meter.start()
     torch.cuda.synchronize()
+    done = [torch.cuda.Event() for _ in range(args.steps)]
     t0 = time.perf_counter()
     for i in range(args.steps):
         pg.pg_sample_group(ctx, seed + 100 + i)
+        done[i].record()                               # queued behind the batch: the host does not wait here
+    for i in range(args.steps):                        # everything is queued; report each batch as it completes
+        done[i].synchronize()
+        progress(f"timed group-batch {i + 1} of {args.steps} done")
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     power = meter.window(t0, t0 + dt)
@@ -425,6 +439,7 @@ def main():
 
     # the same K group-batches once more with every heavy launch bracketed by HIP events on its stream
     # (the brackets cost about a tenth of the loop's wall time, so they stay out of `value`)
+    progress(f"timed region: {dt:.1f} s; event-bracketed pass")
     n_br = max(1, min(args.steps, args.bracket_batches))
     pg.pg_profile_begin(1 << 18)
     torch.cuda.synchronize()
@@ -459,6 +474,7 @@ def main():
                       share_of_step_time=round(s["ms"] * 1e-3 / dt_prof, 4), launches=s["launches"]))
 
     # the HBM-bound kernels at the stress shape (1024 trajectories of 16x128x128 fp32), outside the timed region
+    progress("streaming and selection kernels at the stress shapes")
     others.update(stream_kernels_at_stress_shape(pg, torch))
     others.update(group_kernels_at_stress_shape(pg, torch, np, workloads))
 
@@ -471,16 +487,20 @@ def main():
                            trajectory_steps_per_group_batch=evals, groups=cfg["P"]),
                roofline=roofline, other_kernels=others)
     if not args.no_arms:
+        progress("comparison arms (full groups, uniform subset, selection after sampling)")
         out["comparison_arms"] = comparison_arms(pg, torch, workloads, cfg, w, inp, seed, ctx, buf)
+        progress("importance-ratio pass")
         out["policy_ratio"] = policy_ratio_pass(pg, torch, cfg, w, inp, seed)
     if power:
         out["power"] = dict(socket_cap_w=meter.cap_w, timed_region_mean_w=power["mean_w"], timed_region_max_w=power["max_w"],
                             source="hwmon power1_input polled at 50 Hz by a host thread")
     if args.power_legs:
+        progress("sustained legs with socket power")
         out["power_legs"] = power_legs(pg, torch, meter, [(8192, 8192, 8192), (56544, 4608, 1536), (56544, 1536, 6144)])
     meter.stop()
     if not args.no_cpu_baseline:
         budget = args.cpu_sample or {"cfg1": 8, "cfg2": 8}.get(args.workload, 1)
+        progress(f"oracle on the host cores: {budget} trajectory(ies), one whole step")
         out["cpu_baseline"] = cpu_baseline(cfg, w, inp, seed, budget)
     pg.pg_destroy(ctx)
     print(json.dumps(out), flush=True)
