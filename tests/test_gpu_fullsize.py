@@ -7,13 +7,10 @@ import torch
 
 from oracle import dit, philox, sampler, ovf
 from paper_2512_15347_amd import workloads
+from progress import say            # not captured: these tests run for minutes
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-
-
-def say(msg):
-    print(msg, flush=True)
 
 
 # ------------------------------------------------------------------ config 5: stress shapes
