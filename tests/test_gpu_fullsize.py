@@ -153,7 +153,7 @@ def _free_run(lib, cfg, ctx, buf, seed):
         assert np.all(ids[b:e] // N == g)
         assert abs(adv[b:e].mean()) < 1e-5 and abs(adv[b:e].std() - 1) < 1e-3
     np.testing.assert_allclose(adv, ovf.group_advantages(rew, st["offsets"], 1e-6), rtol=1e-4, atol=1e-5)
-    rec.update(ids=ids, st=st, rewards=rew, logp_hist=hist.astype(np.float64),
+    rec.update(ids=ids, st=st, rewards=rew, logp_hist=hist.astype(np.float64), logp_hist32=hist.copy(),
                logp_sum=buf.logp_sum.cpu().numpy().astype(np.float64))
     return rec
 
@@ -221,6 +221,23 @@ def _compare_followed(cfg, inp, buf, rec, want, ids):
         assert err_p < 2e-2 and err_r < 2e-2 and own < 1e-3 * max(abs(want["reward"][j]), final_sigma)
 
 
+def _one_call_loop_is_the_stepwise_loop(lib, cfg, ctx, buf, rec, seed):
+    """pg_sample_group, the call bench.py times, against the stage-by-stage run above: same launches in the same order,
+    so every output is bit-identical."""
+    M = rec["st"]["M"]
+    x_step = buf.x[rec["st"]["cur_x"]][:M].clone()
+    adv_step = buf.adv[:M].clone()
+    lib.pg_sample_group(ctx, seed)
+    lib.pg_check(ctx)
+    st = lib.pg_state(ctx, cfg["P"])
+    assert st["M"] == M and st["offsets"] == rec["st"]["offsets"] and st["evals"] == rec["st"]["evals"]
+    assert torch.equal(buf.orig_id[st["cur_id"]][:M].cpu(), torch.from_numpy(rec["ids"]))
+    assert torch.equal(buf.x[st["cur_x"]][:M], x_step)
+    assert torch.equal(buf.adv[:M], adv_step)
+    np.testing.assert_array_equal(buf.logp_hist.cpu().numpy().view(np.uint32), rec["logp_hist32"].view(np.uint32))
+    say("  pg_sample_group reproduces the stage-by-stage loop bit for bit")
+
+
 def _same_weights_log_ratio(lib, cfg, tables, ctx, buf, rec):
     """Eq. 19 at full width with the weights that sampled: every log-ratio is 0 up to the fp32 rounding of the
     stored states, |log r| <~ sqrt(d) ulp(x) / C_s."""
@@ -253,6 +270,7 @@ def test_cfg2_full_size(lib):
     say(f"  oracle follows trajectories {ids}")
     want = _follow_in_oracle(cfg, w, inp, tables, seed, ids)
     _compare_followed(cfg, inp, buf, rec, want, ids)
+    _one_call_loop_is_the_stepwise_loop(lib, cfg, ctx, buf, rec, seed)
     lib.pg_destroy(ctx)
 
 
@@ -267,6 +285,7 @@ def test_cfg3_full_size(lib):
     want = _follow_in_oracle(cfg, w, inp, tables, seed, ids)
     _compare_followed(cfg, inp, buf, rec, want, ids)
     _same_weights_log_ratio(lib, cfg, tables, ctx, buf, rec)
+    _one_call_loop_is_the_stepwise_loop(lib, cfg, ctx, buf, rec, seed)
     lib.pg_destroy(ctx)
 
 
@@ -291,4 +310,5 @@ def test_cfg4_full_size(lib):
     say(f"  oracle follows trajectory {ids}")
     want = _follow_in_oracle(cfg, w, inp, tables, seed, ids)
     _compare_followed(cfg, inp, buf, rec, want, ids)
+    _one_call_loop_is_the_stepwise_loop(lib, cfg, ctx, buf, rec, seed)
     lib.pg_destroy(ctx)
