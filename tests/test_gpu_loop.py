@@ -307,3 +307,41 @@ def test_sample_group_is_repeatable_and_seed_dependent(lib):
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
     assert not torch.equal(outs[0][0], outs[2][0])
     lib.pg_destroy(ctx)
+
+
+def test_whole_loop_replays_from_a_hip_graph(lib):
+    """The one-call loop copies nothing from the host and never waits for the device, so it can be recorded into a
+    HIP graph (a caller that must not pay 2 400 launches per tiny group does that).  Every replay, with eager work
+    of the library and synchronisations in between, must give the eager loop's result bit for bit."""
+    name, seed = "cfg1", 4242
+    say(f"graph capture {name}")
+    cfg = workloads.get_config(name)
+    w = workloads.make_weights(cfg); inp = workloads.make_inputs(cfg, w)
+    ctx, buf = _gpu_ctx(lib, cfg, w, inp)
+    P = cfg["P"]
+    lib.pg_sample_group(ctx, seed)                       # eager: also warms every one-time set-up of the launches
+    lib.pg_check(ctx)
+    st = lib.pg_state(ctx, P)
+    M = st["M"]
+    want = dict(x=buf.x[st["cur_x"]][:M].clone(), adv=buf.adv[:M].clone(), hist=buf.logp_hist.clone(),
+                ids=buf.orig_id[st["cur_id"]][:M].clone(), masks=buf.masks.clone())
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        lib.pg_sample_group(ctx, seed)                   # launches go to the capturing stream
+        graph.capture_end()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        # eager work of the library between the replays, with another seed, so that a replay cannot pass on leftovers
+        lib.pg_sample_group(ctx, seed + 1 + rep)
+        lib.pg_check(ctx)
+        assert not torch.equal(buf.x[lib.pg_state(ctx, P)["cur_x"]][:M], want["x"])
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(buf.x[st["cur_x"]][:M], want["x"]), rep
+        assert torch.equal(buf.adv[:M], want["adv"]) and torch.equal(buf.masks, want["masks"])
+        assert torch.equal(buf.orig_id[st["cur_id"]][:M], want["ids"])
+        assert torch.equal(buf.logp_hist.view(torch.int32), want["hist"].view(torch.int32))
+        assert int(buf.status[0]) == 0
+    lib.pg_destroy(ctx)
