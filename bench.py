@@ -367,6 +367,42 @@ def recorded_gemm_traffic(workload):
     return int(m_t.group(1)) if h.hexdigest() == m_h.group(1) else None
 
 
+def gemm_algorithmic_bytes(cfg):
+    """Bytes a GEMM launch of the network must move at least (each operand read once, the output written once, the
+    residual stream read and written by the launches that add into it), averaged over the launches of one group-batch:
+    the figure the counter-measured roofline.traffic stands beside.  Returns (bytes per launch, launches)."""
+    D, C, L_i, Lc, kind = cfg["D"], cfg["C"], cfg["Li"], cfg["Lc"], cfg["kind"]
+    Kp = (4 * C + 63) // 64 * 64
+    joint = kind in ("joint", "mmdit")
+    total = 0.0
+    launches = 0
+
+    def gemm(rows, n, k, out_bytes_per_elem):
+        nonlocal total, launches
+        total += 2.0 * rows * k + 2.0 * n * k + out_bytes_per_elem * rows * n
+        launches += 1
+
+    active = [cfg["N"]] * cfg["P"]
+    for s_ in range(cfg["T"]):
+        M = sum(active)
+        Ri = M * L_i
+        streams = [M * (L_i + (Lc if joint else 0))] if kind != "mmdit" else [Ri, M * Lc]
+        gemm(Ri, D, Kp, 4)                                    # patch embedding into the fp32 residual stream
+        for _ in range(cfg["blocks"]):
+            for R in streams:
+                gemm(R, 3 * D, D, 2)                          # q | k | v
+                gemm(R, D, D, 8)                              # output projection, residual read + write
+                if kind == "cross":
+                    gemm(R, D, D, 2)                          # cross-attention queries
+                    gemm(R, D, D, 8)                          # cross-attention output, residual read + write
+                gemm(R, 4 * D, D, 2)                          # MLP up, GELU
+                gemm(R, D, 4 * D, 8)                          # MLP down, residual read + write
+        gemm(Ri, 4 * C, D, 4)                                 # final projection into the latent layout
+        for g in range(cfg["P"]):
+            active[g] = dict(cfg["schedule"][g]).get(s_, active[g])
+    return total / launches, launches
+
+
 def workloads_evals(cfg):
     from paper_2512_15347_amd import workloads
     return workloads.network_evals(cfg)
@@ -459,6 +495,7 @@ def main():
     roofline = dict(bound="mfma", kernel="gemm_kernel (bf16 MFMA GEMM, all epilogues)", achieved=round(gemm_tflops, 2),
                     peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=round(gemm_tflops / PEAK_BF16_TFLOPS, 4),
                     traffic=recorded_gemm_traffic(args.workload),
+                    traffic_algorithmic=round(gemm_algorithmic_bytes(cfg)[0]),
                     launches=g["launches"], avg_launch_us=round(1e3 * g["ms"] / max(g["launches"], 1), 2),
                     share_of_step_time=round(g["ms"] * 1e-3 / dt_prof, 4), bracketed_batches=n_br,
                     bracketed_pass_ms_per_step=round(1e3 * dt_prof / n_br, 3))
