@@ -11,7 +11,7 @@ for _p in (ROOT, os.path.dirname(os.path.abspath(__file__))):
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
-    import progress
+    import pg_progress as progress
     progress.set_config(config)
     from paper_2512_15347_amd.build import ensure_built
     ensure_built()                                   # compiles only when no library has been built yet

@@ -7,7 +7,7 @@ import torch
 
 from oracle import dit, philox, sampler, ovf
 from paper_2512_15347_amd import workloads
-from progress import say            # not captured: these tests run for minutes
+from pg_progress import say            # not captured: these tests run for minutes
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
