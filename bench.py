@@ -503,6 +503,8 @@ def main():
     reg = mfma_register_loop(pg, torch)
     roofline["mfma_register_loop"] = reg
     roofline["frac_of_register_loop_random"] = round(gemm_tflops / reg["random_tflops"], 4) if reg["random_tflops"] > 0 else None
+    roofline["note"] = ("with N(0,1)-like operands this GEMM draws the socket power cap at every shape and the clock drops with MFMA activity: "
+                        "the figure is set by energy per flop, see profiles/power_telemetry_cfg3_loop_and_gemm_alone.txt and the `power` object")
     others = dict(
         attention=dict(tflops=round(a["work"] / (a["ms"] * 1e-3) / 1e12, 2) if a["ms"] > 0 else None,
                        share_of_step_time=round(a["ms"] * 1e-3 / dt_prof, 4), launches=a["launches"]),
