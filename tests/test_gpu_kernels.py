@@ -161,7 +161,7 @@ def test_compact_gather_is_bit_exact(lib):
 # ------------------------------------------------------------------ OVF
 def _run_ovf(lib, rewards, offsets, ks):
     P = len(ks)
-    total = int(np.sum(ks))
+    total = int(np.sum(np.maximum(ks, 0)))          # a negative count reserves no slots
     masks = torch.zeros(P, dtype=torch.int64, device=DEV)
     sel = torch.full((max(total, 1),), -1, dtype=torch.int32, device=DEV)
     newoff = torch.zeros(P + 1, dtype=torch.int32, device=DEV)
@@ -278,6 +278,13 @@ def test_ovf_flags_non_finite_and_bad_counts(lib):
     r[1] = 0.2
     masks, sel, newoff, status = _run_ovf(lib, r, [0, 4, 8], [5, 2])   # k > n
     assert status & 2 and masks[0] == 0
+    # the five slots reserved for the bad group hold rows of that group, and the clean group behind it is intact
+    assert newoff.tolist() == [0, 5, 7] and set(sel[:5].tolist()) <= {0, 1, 2, 3}
+    assert sel[5:7].tolist() == [4 + i for i in range(4) if (int(masks[1]) >> i) & 1]
+    # a negative count reserves nothing: the groups behind it keep non-negative offsets
+    masks, sel, newoff, status = _run_ovf(lib, r, [0, 4, 8], [-3, 2])
+    assert status & 2 and masks[0] == 0 and newoff.tolist() == [0, 0, 2]
+    assert masks[1] == np.uint64(ovf.ovf_select(r[4:], 2)[0])
     masks, sel, newoff, status = _run_ovf(lib, r, [0, 0, 8], [0, 3])   # an empty group is fine
     assert status == 0 and masks[0] == 0 and newoff.tolist() == [0, 0, 3]
 
