@@ -82,6 +82,22 @@ __device__ __forceinline__ uint2 pack_bf16x4(float4 v) {
   return r;
 }
 
+// f(tag<I>), f(tag<I + 2>), ... while I < N and f returns true
+template <int I> struct int_tag { static constexpr int value = I; };
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for_by2(F&& f) {
+  if constexpr (I < N) {
+    if (f(int_tag<I>{})) static_for_by2<I + 2, N>(f);
+  }
+}
+
+// orders this wave's LDS accesses around a hand-over between its lanes (LDS serves one wave's accesses in issue order;
+// this keeps the compiler from moving them across the hand-over)
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __builtin_bit_cast(float, (uint32_t)b << 16); }
 __device__ __forceinline__ uint16_t f32_to_bf16(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
 
@@ -92,31 +108,12 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;   // 32x32 MFMA tiles per wave
   constexpr int A_BYTES = BM * BK * 2, W_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + W_BYTES;
   extern __shared__ __align__(16) unsigned char smem[];
-  // ---- the problem this block works on.  Value channels (EPI_VT, and the columns >= v_start of
-  // EPI_QKV) are produced TRANSPOSED by swapping the operand roles: rows of the block's problem are
-  // the value channels n (operand "A" = their weight rows), its columns are the tokens (operand "W" =
-  // the activations), so that consecutive output columns are consecutive tokens of one row of V^T. ----
-  const uint16_t* PA = a.A; int64_t LDA = a.lda;
-  const uint16_t* PW = a.W; int64_t LDW = a.ldw;
+  const uint16_t* PA = a.A; const int64_t LDA = a.lda;
+  const uint16_t* PW = a.W; const int64_t LDW = a.ldw;
   const uint16_t* PB = a.bias;
-  int MM = a.M, NN = a.N;
-  bool vt_block = false;
+  const int MM = a.M, NN = a.N;
   const int per_xcd = gridDim.x / XCDS;
-  int b = a.raster ? (blockIdx.x % XCDS) * per_xcd + blockIdx.x / XCDS : blockIdx.x;
-  if (EPI == EPI_QKV || EPI == EPI_VT) {
-    const int vs = (EPI == EPI_VT) ? 0 : a.v_start;
-    const int tiles1 = ((a.M + BM - 1) / BM) * ((vs + BN - 1) / BN);
-    if (b < tiles1) {
-      NN = vs;
-    } else {
-      b -= tiles1;
-      vt_block = true;
-      PA = a.W + (int64_t)vs * a.ldw; LDA = a.ldw;
-      PW = a.A; LDW = a.lda;
-      PB = a.bias ? a.bias + vs : nullptr;
-      MM = a.N - vs; NN = a.M;
-    }
-  }
+  const int b = a.raster ? (blockIdx.x % XCDS) * per_xcd + blockIdx.x / XCDS : blockIdx.x;
   // ---- which output tile: XCD-aware, banded raster ----
   const int tiles_m = (MM + BM - 1) / BM, tiles_n = (NN + BN - 1) / BN;
   const int total = tiles_m * tiles_n;
@@ -249,51 +246,89 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void gemm_kernel(const GemmArgs
     float* stg = reinterpret_cast<float*>(smem) + wave * (32 * EST);
     const int c4 = (lane % LPR) * 4, rsub = lane / LPR;
     const int n = n0 + wn * (BN / WN) + c4;
-    if ((EPI == EPI_QKV || EPI == EPI_VT) && vt_block) {
-      // V^T[traj][channel][token]: rows of this block are channels, the lane's 4 columns are tokens
-      // n .. n+3; they are stored as two bf16 pairs when they sit in one trajectory at an even offset
-      const int Dv = MM;
-      const int traj0 = n / a.L, tok0 = n - traj0 * a.L;
-      const bool whole = n + 3 < NN && tok0 + 3 < a.L && ((tok0 + a.tok_off) & 1) == 0;
+    // columns written row-major: all of them, except the value channels of EPI_QKV
+    const int n_rm = EPI == EPI_QKV ? a.v_start : NN;
+    if (EPI == EPI_QKV) {
+      // ---- value channels, stored TRANSPOSED: V^T[traj][channel][token].  In an accumulator tile a lane already
+      // holds 4 consecutive tokens of ONE channel, so they are packed to bf16 and staged channel-major (8 bytes per
+      // LDS write), two 32-token slabs at a time; then a lane owns 4 consecutive tokens of a channel row and 16
+      // lanes write 64 consecutive tokens (128 bytes) of it.  A 32-column accumulator tile is either all value
+      // channels or none (v_start is a multiple of 32). ----
+      constexpr int VP = 72;                         // staging pitch in bf16: 64 tokens + 8 (rows stay 16-byte aligned)
+      static_assert(TN * 32 * VP * 2 <= 32 * EST * 4, "the transposed staging fits the wave's staging area");
+      uint16_t* stg16 = reinterpret_cast<uint16_t*>(stg);
+      const int col_w = n0 + wn * (BN / WN);         // first column of this wave
+      const int Dv = NN - n_rm;
+      bool is_v[TN];
+      float vb[TN];
+      bool any_v = false;
 #pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        const int slab0 = m0 + wm * (BM / WM) + i * 32;
-        if (slab0 >= MM) break;
+      for (int j = 0; j < TN; ++j) {
+        const int col = col_w + j * 32;
+        is_v[j] = col >= n_rm && col < NN;           // wave-uniform
+        any_v = any_v || is_v[j];
+        vb[j] = (is_v[j] && PB) ? bf16_to_f32(PB[col + l32]) : 0.f;
+      }
+      if (any_v) {
+        static_for_by2<0, TM>([&](auto tag) {
+          constexpr int i0 = decltype(tag)::value;
+          constexpr int nsl = i0 + 1 < TM ? 2 : 1;   // slabs staged together
+          const int row0 = m0 + wm * (BM / WM) + i0 * 32;        // first token row of the group, wave-uniform
+          if (row0 >= MM) return false;
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+          for (int ii = 0; ii < 2; ++ii) {
+            if (ii >= nsl) break;
 #pragma unroll
-          for (int q = 0; q < 4; ++q)
+            for (int j = 0; j < TN; ++j) {
+              if (!is_v[j]) continue;
 #pragma unroll
-            for (int t = 0; t < 4; ++t) stg[(8 * q + 4 * half + t) * EST + j * 32 + l32] = acc[i][j][4 * q + t];
-#pragma unroll
-        for (int p = 0; p < NP; ++p) {
-          const int ch = slab0 + RPI * p + rsub;                 // value channel (row of the block)
-          float4 v = *reinterpret_cast<const float4*>(stg + (RPI * p + rsub) * EST + c4);
-          if (ch >= MM || n >= NN) continue;
-          const float bv = PB ? bf16_to_f32(PB[ch]) : 0.f;
-          v.x += bv; v.y += bv; v.z += bv; v.w += bv;
-          if (whole) {
-            uint32_t* dst = reinterpret_cast<uint32_t*>(a.vt + ((int64_t)traj0 * Dv + ch) * a.Lpad + a.tok_off + tok0);
-            const uint2 pk = pack_bf16x4(v);
-            dst[0] = pk.x;
-            dst[1] = pk.y;
-          } else {
-            const float e[4] = {v.x, v.y, v.z, v.w};
-            int traj = traj0, tok = tok0;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-              if (n + k < NN) {
-                if (tok >= a.L) { tok -= a.L; ++traj; }
-                a.vt[((int64_t)traj * Dv + ch) * a.Lpad + a.tok_off + tok] = f32_to_bf16(e[k]);
-                ++tok;
+              for (int q = 0; q < 4; ++q) {
+                const float4 v = {acc[i0 + ii][j][4 * q] + vb[j], acc[i0 + ii][j][4 * q + 1] + vb[j],
+                                  acc[i0 + ii][j][4 * q + 2] + vb[j], acc[i0 + ii][j][4 * q + 3] + vb[j]};
+                *reinterpret_cast<uint2*>(stg16 + (j * 32 + l32) * VP + ii * 32 + 8 * q + 4 * half) = pack_bf16x4(v);
               }
             }
           }
-        }
+          wave_lds_sync();
+          constexpr int lpr = 8 * nsl, rpa = 64 / lpr;   // lanes per channel row, channel rows per access
+          const int t4 = (lane % lpr) * 4, csub = lane / lpr;
+          const int r = row0 + t4;                   // the lane's first token row
+          const int traj0 = r / a.L, tok0 = r - traj0 * a.L;
+          const bool whole = r + 3 < MM && tok0 + 3 < a.L && ((tok0 + a.tok_off) & 1) == 0;
+#pragma unroll
+          for (int p = 0; p < TN * 32 / rpa; ++p) {
+            const int cl = p * rpa + csub;           // channel row inside the wave's columns
+            if (!is_v[cl / 32] || r >= MM) continue;
+            const uint2 pk = *reinterpret_cast<const uint2*>(stg16 + cl * VP + t4);
+            const int ch = col_w + cl - n_rm;
+            uint16_t* dst = a.vt + ((int64_t)traj0 * Dv + ch) * a.Lpad + a.tok_off + tok0;
+            if (whole) {
+              if (((uintptr_t)dst & 7) == 0) {
+                store_stream(dst, pk);
+              } else {
+                reinterpret_cast<uint32_t*>(dst)[0] = pk.x;
+                reinterpret_cast<uint32_t*>(dst)[1] = pk.y;
+              }
+            } else {
+              const uint16_t e[4] = {(uint16_t)pk.x, (uint16_t)(pk.x >> 16), (uint16_t)pk.y, (uint16_t)(pk.y >> 16)};
+              int traj = traj0, tok = tok0;
+#pragma unroll
+              for (int k = 0; k < 4; ++k) {
+                if (r + k < MM) {
+                  if (tok >= a.L) { tok -= a.L; ++traj; }
+                  a.vt[((int64_t)traj * Dv + ch) * a.Lpad + a.tok_off + tok] = e[k];
+                  ++tok;
+                }
+              }
+            }
+          }
+          wave_lds_sync();
+          return true;
+        });
       }
-      return;
+      if (col_w >= n_rm) return;                     // nothing row-major in this wave's columns
     }
-    const bool n_ok = n < NN;                        // N is a multiple of 4
+    const bool n_ok = n < n_rm;                      // N is a multiple of 4
     const float col_scale = n < a.scale_cols ? a.out_scale : 1.f;   // e.g. queries pre-multiplied by the softmax scale
     float4 ng4 = {1.f, 1.f, 1.f, 1.f};               // norm scales of this lane's 4 columns
     if (EPI == EPI_QKV && a.norm_hd > 0 && n_ok) {
@@ -436,11 +471,7 @@ static pg_status launch_tile(const GemmArgs& a, hipStream_t s) {
                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS));
     attr_set = true;
   }
-  int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-  if (EPI == EPI_QKV || EPI == EPI_VT) {           // row-major part + role-swapped value part (see the kernel)
-    const int vs = (EPI == EPI_VT) ? 0 : a.v_start;
-    tiles = ((a.M + BM - 1) / BM) * ((vs + BN - 1) / BN) + ((a.N - vs + BM - 1) / BM) * ((a.M + BN - 1) / BN);
-  }
+  const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
   const int grid = (tiles + XCDS - 1) / XCDS * XCDS;
   gemm_kernel<EPI, BM, BN, BK, WM, WN, MINW, NST><<<dim3(grid), dim3(64 * WM * WN), LDS, s>>>(a);
   PG_LAUNCH_CHECK("gemm_kernel");
@@ -452,12 +483,8 @@ static pg_status launch_tile(const GemmArgs& a, hipStream_t s) {
 // Pick the shape with the best product of slot occupancy and the measured relative speed of its main
 // loop.
 static int pick_tile(const GemmArgs& a, int epilogue) {
-  // columns written row-major / produced through swapped operand roles (their tiles are BM channels x BN rows)
-  const int n_rm = epilogue == EPI_VT ? 0 : epilogue == EPI_QKV ? a.v_start : a.N;
-  const int n_sw = a.N - n_rm;
   auto score = [&](int bm, int bn, int per_cu, double speed) {
-    const double tiles = (double)((a.M + bm - 1) / bm) * ((n_rm + bn - 1) / bn) +
-                         (double)((n_sw + bm - 1) / bm) * ((a.M + bn - 1) / bn);
+    const double tiles = (double)((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn);
     const double slots = 256.0 * per_cu;
     const double useful = (double)a.M * a.N / ((double)bm * bn);      // ragged edge tiles do less work
     return speed * useful / (ceil(tiles / slots) * slots);
@@ -492,7 +519,7 @@ pg_status launch_gemm(const GemmArgs& a_in, int epilogue, hipStream_t s) {
   if (a.lda % 8 || a.ldw % 8 || a.lda < a.K || a.ldw < a.K || ((uintptr_t)a.A & 15) || ((uintptr_t)a.W & 15))
     return fail(PG_ESHAPE, "GEMM operands need 16-byte aligned rows (lda %lld, ldw %lld)", (long long)a.lda, (long long)a.ldw);
   if (!a.A || !a.W) return fail(PG_EINVAL, "GEMM: null operand");
-  if (epilogue != EPI_UNPATCH && epilogue != EPI_VT) {
+  if (epilogue != EPI_UNPATCH) {
     // the row-major epilogues write 4 consecutive columns per lane
     const int n_rm = epilogue == EPI_QKV ? a.v_start : a.N;
     if (n_rm % 4) return fail(PG_ESHAPE, "GEMM N = %d must be a multiple of 4", n_rm);
@@ -506,9 +533,10 @@ pg_status launch_gemm(const GemmArgs& a_in, int epilogue, hipStream_t s) {
         ((uintptr_t)a.qn_g & 7) || ((uintptr_t)a.kn_g & 7))
       return fail(PG_ESHAPE, "GEMM: bad fused head norm (width %d)", a.norm_hd);
   }
-  if (epilogue == EPI_QKV || epilogue == EPI_VT) {
-    if (!a.vt || a.L < 1 || a.Lpad < a.L || (a.Lpad & 1) || ((uintptr_t)a.vt & 3) ||
-        (epilogue == EPI_QKV && (a.v_start < 0 || a.v_start > a.N || !a.outb)))
+  if (epilogue == EPI_QKV) {
+    const int vs = a.v_start;
+    if (!a.vt || a.L < 1 || a.Lpad < a.L || (a.Lpad & 1) || ((uintptr_t)a.vt & 3) || vs < 0 || vs > a.N || vs % 32 ||
+        (a.N - vs) % 32 || !a.outb)
       return fail(PG_ESHAPE, "GEMM: bad transposed-value output (L %d, Lpad %d, v_start %d)", a.L, a.Lpad, a.v_start);
   }
   const int rec = prof_open(PROF_GEMM, 2.0 * a.M * (double)a.N * (a.k_algo > 0 ? a.k_algo : a.K), s);
@@ -517,7 +545,6 @@ pg_status launch_gemm(const GemmArgs& a_in, int epilogue, hipStream_t s) {
     case EPI_F32: st = launch_one<EPI_F32>(a, s); break;
     case EPI_EMBED: st = launch_one<EPI_EMBED>(a, s); break;
     case EPI_BF16: st = launch_one<EPI_BF16>(a, s); break;
-    case EPI_VT: st = launch_one<EPI_VT>(a, s); break;
     case EPI_QKV: st = launch_one<EPI_QKV>(a, s); break;
     case EPI_GELU: st = launch_one<EPI_GELU>(a, s); break;
     case EPI_RESID: st = launch_one<EPI_RESID>(a, s); break;

@@ -8,10 +8,10 @@ enum GemmEpilogue {
   EPI_F32 = 0,      // outf[r, n] = acc + bias
   EPI_EMBED = 1,    // outf[(r / Li) * L + r % Li, n] = acc + bias + pos[r % Li, n]     (patch embedding)
   EPI_BF16 = 2,     // outb[r, n] = bf16(acc + bias)
-  EPI_QKV = 3,      // columns n < v_start as EPI_BF16, columns n >= v_start as EPI_VT, one launch
+  EPI_QKV = 3,      // columns n < v_start as EPI_BF16; value channels n >= v_start are stored transposed:
+                    // vt[((r / L) * (N - v_start) + n - v_start) * Lpad + tok_off + r % L] = bf16(acc + bias)
   EPI_GELU = 4,     // outb[r, n] = bf16(gelu_tanh(acc + bias))
   EPI_RESID = 5,    // outf[r, n] += gate[group_of[r / L], n] * (acc + bias)   (gate NULL: plain add)
-  EPI_VT = 7,       // vt[((r / L) * N + n) * Lpad + r % L] = bf16(acc + bias)   (values stored transposed)
   EPI_UNPATCH = 6   // u[m, c, 2 py + dy, 2 px + dx] = acc + bias, r = m * Li + py * Wp + px, n = 4 c + 2 dy + dx
 };
 
