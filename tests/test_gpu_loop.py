@@ -202,6 +202,35 @@ def test_network_output_at_step_0(lib, name):
     lib.pg_destroy(ctx)
 
 
+@pytest.mark.parametrize("P,N,tile_rows", [(5, 51, 192), (5, 42, 160), (6, 49, 224)])
+def test_network_output_with_every_tile_height_of_the_projection(lib, P, N, tile_rows):
+    """The fused query / key / value projection stages its value channels through LDS in groups of two 32-row
+    slabs; tiles of 192, 160 and 224 rows end in a single slab.  Row counts P * N * 64 chosen so that the
+    launcher picks that height for the 768-column projection (255, 252 and 252 tiles for 256 compute units);
+    sampled trajectories (first, last, and two whose rows straddle tile boundaries) against the oracle."""
+    from oracle import dit, philox
+    say(f"network forward with {P * N * 64} rows ({tile_rows}-row tiles in the projection)")
+    seed = workloads.MASTER_SEED
+    cfg = workloads.get_config("cfg1")
+    cfg.update(P=P, N=N, D=256, heads=4, T=2, schedule=[[] for _ in range(P)])
+    w = workloads.make_weights(cfg)
+    inp = workloads.make_inputs(cfg, w)
+    tables = sampler.flow_sde_tables(cfg["T"], cfg["sampler"]["a"])
+    ctx, buf = _gpu_ctx(lib, cfg, w, inp)
+    lib.pg_init_group(ctx, seed)
+    lib.pg_net_forward(ctx, 0)
+    torch.cuda.synchronize()
+    u_gpu = buf.u.cpu().numpy().astype(np.float64)
+    M = P * N
+    for i in sorted({0, 2, tile_rows // 64, M // 2, M - 1}):  # trajectory tile_rows // 64 holds the first tile boundary
+        x0 = philox.normals(seed, philox.STREAM_INIT, i, 0, cfg["d"])[None]
+        u = dit.forward(w, cfg, x0, tables["t_in"][0], inp["y"][i // N], None)
+        err = np.max(np.abs(u_gpu[i].reshape(-1) - u[0].reshape(-1))) / np.max(np.abs(u[0]))
+        say(f"  trajectory {i}: max err / max|u| = {err:.2e}")
+        assert err < 2e-2
+    lib.pg_destroy(ctx)
+
+
 @pytest.mark.parametrize("name", ["cfg1", "cfg2_small", "cfg3_small", "cfg4_small", "cfg3_mmdit_small"])
 def test_full_loop_with_own_network(lib, name):
     """Free-running library loop against the free-running oracle: the survivor sets must be the
